@@ -1,0 +1,131 @@
+/*
+ * metro.h -- C ABI of the MI355X (gfx950) METRO hot path.
+ *
+ * METRO = Minimum Expert Token ROuting (arxiv 2512.09277): choose one replica for every
+ * (token, expert) pair so that the maximum number of *activated* expert replicas on any
+ * expert-parallel rank is minimised (problem min-exp-routing, Sec. 4.1), then run the
+ * memory-bound decode MoE layer of one rank on the pairs routed to it.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller; nothing is allocated,
+ *     freed or synchronised inside.  Work is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and the call returns at once.
+ *   - Return value: METRO_OK or a negative METRO_ERR_* for arguments the host can check.
+ *     On error nothing is enqueued.  Conditions only the device can see (an id out of
+ *     range, an expert with tokens but no replica) are reported through `err_flag`.
+ *   - Notation: N experts, top-k, G logical EP ranks, spr replica slots per rank,
+ *     S = G*spr slots, slot s lives on rank s / spr; T tokens in the (global) batch;
+ *     pair index p = t*k + j; H hidden size, I intermediate size.
+ *   - Limits: 1 <= N <= 512, 1 <= G <= 64, 1 <= spr <= 64, S <= 2048, 1 <= k <= N,
+ *     T*k < 2^24.
+ */
+#ifndef METRO_H_
+#define METRO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define METRO_OK 0
+#define METRO_ERR_INVALID_ARG (-1)   /* null pointer, non-positive size, k > N, misaligned pointer */
+#define METRO_ERR_UNSUPPORTED (-2)   /* a size beyond the limits above, unknown dtype */
+#define METRO_ERR_WORKSPACE (-3)     /* workspace smaller than the *_workspace_bytes() figure */
+#define METRO_ERR_HIP (-4)           /* the HIP runtime refused a launch */
+
+/* bits of err_flag[layer] */
+#define METRO_FLAG_BAD_ID 1          /* a top-k id outside [-1, N) */
+#define METRO_FLAG_NO_REPLICA 2      /* an expert that has tokens is on no rank */
+#define METRO_FLAG_BAD_PLACEMENT 4   /* a slot_to_expert entry outside [-1, N) */
+
+#define METRO_DTYPE_F32 0
+#define METRO_DTYPE_BF16 1
+
+/* Text for a METRO_ERR_* code (static storage). */
+const char* metro_status_string(int status);
+
+/*
+ * metro_route -- the greedy solve of min-exp-routing (Alg. 1, Sec. 4.3) for L independent
+ * layers in one launch.  Experts are served in ascending id; each expert with at least one
+ * pair (T[i] > 0) takes, among the ranks hosting it, the one with the fewest activated
+ * experts so far, ties to the lowest rank; all of its pairs go to that replica (x from y,
+ * Sec. 4.3).  The result is a deterministic, lock-free execution of Alg. 1.
+ *
+ *   topk_ids       [L,T,k] int32  global top-k expert ids of the whole batch; -1 = padded pair
+ *   slot_to_expert [L,S]   int32  placement (matrix A of Sec. 4.1): expert held by each slot,
+ *                                 -1 = empty slot; a second copy of an expert on the same rank
+ *                                 is ignored (A is binary)
+ *   pair_slot      [L,T,k] int32  out: chosen slot of every pair (-1 for padded pairs)
+ *   expert_slot    [L,N]   int32  out: activated slot of every expert, -1 if it has no pair
+ *   rank_active    [L,G]   int32  out: activated experts per rank (lambda = their maximum)
+ *   rank_bitmap    [L,G]   uint64 out: bit l set iff local slot l of the rank is activated
+ *   err_flag       [L]     int32  out: 0, or METRO_FLAG_* bits; outputs of a flagged layer are
+ *                                 unspecified apart from being in range
+ */
+int metro_route(const int32_t* topk_ids, const int32_t* slot_to_expert, int L, int T, int k, int N, int G,
+                int spr, int32_t* pair_slot, int32_t* expert_slot, int32_t* rank_active,
+                uint64_t* rank_bitmap, int32_t* err_flag, void* stream);
+
+/*
+ * metro_route_token_balanced -- the baseline the paper compares with (EPLB-style routing,
+ * Sec. 2.3 and Sec. 6.1 "Compared baselines"): every expert's pairs are spread evenly over
+ * its replicas.  The q-th pair of an expert, in flattened (t, j) order, goes to replica
+ * q mod r, replicas taken in ascending slot id.  Same arguments as metro_route, without
+ * expert_slot (an expert may activate several replicas).
+ */
+int metro_route_token_balanced(const int32_t* topk_ids, const int32_t* slot_to_expert, int L, int T, int k,
+                               int N, int G, int spr, int32_t* pair_slot, int32_t* rank_active,
+                               uint64_t* rank_bitmap, int32_t* err_flag, void* stream);
+
+/*
+ * moe_permute -- per-replica token lists of one rank ("route tokens", Sec. 4.3): the pairs
+ * whose slot lies on `rank`, ordered by local slot l = slot - rank*spr and, within a slot,
+ * by pair index (a stable counting sort).
+ *
+ *   pair_slot     [T,k]   int32  one layer's routing result
+ *   group_offsets [spr+1] int32  out: rows of local slot l are [group_offsets[l], group_offsets[l+1])
+ *   perm_pair     [T*k]   int32  out: pair index of every row; entries past n_pairs are not written
+ *   pair_row      [T,k]   int32  out: row of each pair in the list, -1 if routed to another rank
+ *   n_pairs       [1]     int32  out: number of rows (= group_offsets[spr])
+ */
+int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32_t* group_offsets,
+                int32_t* perm_pair, int32_t* pair_row, int32_t* n_pairs, void* stream);
+
+/*
+ * moe_grouped_ffn -- SwiGLU expert FFN over the token lists of one rank.  Only slots with at
+ * least one row are touched, so HBM weight traffic scales with the number of activated
+ * experts (Sec. 3.2).  For row r of local slot l, token t = perm_pair[r] / k:
+ *     gate = x[t] . w13[l][0:I]^T      up = x[t] . w13[l][I:2I]^T
+ *     y_perm[r] = (silu(gate) * up) . w2[l]^T
+ *
+ *   x      [T,H]       dtype   activations of the whole batch
+ *   w13    [spr,2I,H]  dtype   per local slot: rows 0..I-1 gate, I..2I-1 up (H contiguous)
+ *   w2     [spr,H,I]   dtype   per local slot: down projection (I contiguous)
+ *   y_perm [T*k,H]     dtype   out: rows 0..n_pairs-1 are written
+ *   ws                         workspace of moe_grouped_ffn_workspace_bytes(); 256-byte aligned
+ *   dtype  METRO_DTYPE_BF16: bf16 storage, fp32 accumulation on the matrix cores, the
+ *          intermediate silu(gate)*up rounded to bf16; needs H % 128 == 0 and I % 128 == 0,
+ *          other shapes take a slower general kernel.  METRO_DTYPE_F32: fp32 throughout.
+ *   x, w13, w2, y_perm must be 16-byte aligned.
+ */
+size_t moe_grouped_ffn_workspace_bytes(int T, int k, int spr, int H, int I, int dtype);
+int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
+                    int spr, int H, int I, int dtype, const void* w13, const void* w2, void* y_perm,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * moe_unpermute -- the rank's share of the combine step (Sec. 2.2): for every token,
+ *     out[t] = sum over j ascending of topk_w[t,j] * y_perm[pair_row[t,j]]   (pairs served here),
+ * accumulated in fp32; tokens with no pair on this rank get zeros.
+ *
+ *   y_perm [T*k,H] dtype, pair_row [T,k] int32, topk_w [T,k] float32, out [T,H] dtype.
+ */
+int moe_unpermute(const void* y_perm, const int32_t* pair_row, const float* topk_w, int T, int k, int H,
+                  int dtype, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* METRO_H_ */

@@ -1,0 +1,190 @@
+"""Thin Python binding of libmetro.so (see include/metro.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI; torch supplies device
+memory and the current stream.  There is no CPU fallback: if the library has not been
+built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmetro.so")
+_lib = None
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+FLAG_BAD_ID, FLAG_NO_REPLICA, FLAG_BAD_PLACEMENT = 1, 2, 4
+DTYPE_F32, DTYPE_BF16 = 0, 1
+
+EXPORTS = ("metro_status_string", "metro_route", "metro_route_token_balanced", "moe_permute",
+           "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_unpermute")
+
+
+class MetroError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libmetro: {text} (status {status})")
+        self.status = status
+
+
+def load() -> ctypes.CDLL:
+    """Load the in-tree library; raises if it was not built (python -m paper_2512_09277_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_09277_amd.build` "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        lib.metro_status_string.restype = ctypes.c_char_p
+        lib.metro_status_string.argtypes = [ci]
+        lib.metro_route.restype = ci
+        lib.metro_route.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        lib.metro_route_token_balanced.restype = ci
+        lib.metro_route_token_balanced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp]
+        lib.moe_permute.restype = ci
+        lib.moe_permute.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp]
+        lib.moe_grouped_ffn_workspace_bytes.restype = sz
+        lib.moe_grouped_ffn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        lib.moe_grouped_ffn.restype = ci
+        lib.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        lib.moe_unpermute.restype = ci
+        lib.moe_unpermute.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise MetroError(status, load().metro_status_string(status).decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> int:
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} device tensor, got {t.dtype} on {t.device}")
+    return t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    raise TypeError("activations and weights are bfloat16 or float32")
+
+
+def route_buffers(L: int, T: int, k: int, N: int, G: int, device) -> Dict[str, torch.Tensor]:
+    """Output buffers of the routing calls (reusable across calls of the same shape)."""
+    return dict(pair_slot=torch.empty((L, T, k), dtype=torch.int32, device=device),
+                expert_slot=torch.empty((L, N), dtype=torch.int32, device=device),
+                rank_active=torch.empty((L, G), dtype=torch.int32, device=device),
+                rank_bitmap=torch.empty((L, G), dtype=torch.int64, device=device),
+                err_flag=torch.empty((L,), dtype=torch.int32, device=device))
+
+
+def _route(fn_name: str, topk_ids: torch.Tensor, slot_to_expert: torch.Tensor, N: int, G: int, spr: int,
+           out: Optional[Dict[str, torch.Tensor]]) -> Dict[str, torch.Tensor]:
+    if topk_ids.dim() == 2:
+        topk_ids = topk_ids.unsqueeze(0)
+    if slot_to_expert.dim() == 1:
+        slot_to_expert = slot_to_expert.unsqueeze(0)
+    L, T, k = topk_ids.shape
+    if tuple(slot_to_expert.shape) != (L, G * spr):
+        raise ValueError(f"slot_to_expert must be [L={L}, G*spr={G * spr}]")
+    if out is None:
+        out = route_buffers(L, T, k, N, G, topk_ids.device)
+    lib = load()
+    ids_p = _dev(topk_ids, torch.int32, "topk_ids")
+    s2e_p = _dev(slot_to_expert, torch.int32, "slot_to_expert")
+    ps = _dev(out["pair_slot"], torch.int32, "pair_slot")
+    ra = _dev(out["rank_active"], torch.int32, "rank_active")
+    rb = _dev(out["rank_bitmap"], torch.int64, "rank_bitmap")
+    ef = _dev(out["err_flag"], torch.int32, "err_flag")
+    if fn_name == "metro_route":
+        es = _dev(out["expert_slot"], torch.int32, "expert_slot")
+        _check(lib.metro_route(ids_p, s2e_p, L, T, k, N, G, spr, ps, es, ra, rb, ef, _stream()))
+    else:
+        _check(lib.metro_route_token_balanced(ids_p, s2e_p, L, T, k, N, G, spr, ps, ra, rb, ef, _stream()))
+    return out
+
+
+def metro_route(topk_ids, slot_to_expert, N: int, G: int, spr: int, out=None) -> Dict[str, torch.Tensor]:
+    """topk_ids [L,T,k] (or [T,k]) int32, slot_to_expert [L,S] (or [S]) int32 -> dict of device tensors
+    pair_slot [L,T,k], expert_slot [L,N], rank_active [L,G], rank_bitmap [L,G] (int64 bits), err_flag [L]."""
+    return _route("metro_route", topk_ids, slot_to_expert, N, G, spr, out)
+
+
+def metro_route_token_balanced(topk_ids, slot_to_expert, N: int, G: int, spr: int, out=None):
+    """Same as metro_route for the token-balanced baseline; expert_slot is left untouched."""
+    return _route("metro_route_token_balanced", topk_ids, slot_to_expert, N, G, spr, out)
+
+
+def permute_buffers(T: int, k: int, spr: int, device) -> Dict[str, torch.Tensor]:
+    return dict(group_offsets=torch.empty((spr + 1,), dtype=torch.int32, device=device),
+                perm_pair=torch.empty((T * k,), dtype=torch.int32, device=device),
+                pair_row=torch.empty((T, k), dtype=torch.int32, device=device),
+                n_pairs=torch.empty((1,), dtype=torch.int32, device=device))
+
+
+def moe_permute(pair_slot: torch.Tensor, rank: int, spr: int, out=None) -> Dict[str, torch.Tensor]:
+    """pair_slot [T,k] int32 -> dict(group_offsets [spr+1], perm_pair [T*k], pair_row [T,k], n_pairs [1])."""
+    T, k = pair_slot.shape
+    if out is None:
+        out = permute_buffers(T, k, spr, pair_slot.device)
+    _check(load().moe_permute(_dev(pair_slot, torch.int32, "pair_slot"), T, k, rank, spr,
+                              _dev(out["group_offsets"], torch.int32, "group_offsets"),
+                              _dev(out["perm_pair"], torch.int32, "perm_pair"),
+                              _dev(out["pair_row"], torch.int32, "pair_row"),
+                              _dev(out["n_pairs"], torch.int32, "n_pairs"), _stream()))
+    return out
+
+
+def moe_grouped_ffn_workspace_bytes(T: int, k: int, spr: int, H: int, I: int, dtype: torch.dtype) -> int:
+    code = DTYPE_BF16 if dtype == torch.bfloat16 else DTYPE_F32
+    return int(load().moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, code))
+
+
+def moe_grouped_ffn(x: torch.Tensor, perm_pair: torch.Tensor, group_offsets: torch.Tensor, k: int,
+                    w13: torch.Tensor, w2: torch.Tensor, y_perm: Optional[torch.Tensor] = None,
+                    ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x [T,H], w13 [spr,2I,H], w2 [spr,H,I] (bf16 or f32) -> y_perm [T*k,H] (rows < n_pairs written)."""
+    T, H = x.shape
+    spr, two_i, _ = w13.shape
+    I = two_i // 2
+    if tuple(w13.shape) != (spr, 2 * I, H) or tuple(w2.shape) != (spr, H, I):
+        raise ValueError("weight shapes must be w13 [spr,2I,H] and w2 [spr,H,I]")
+    if perm_pair.numel() < T * k or group_offsets.numel() != spr + 1:
+        raise ValueError("perm_pair must hold T*k entries and group_offsets spr+1")
+    code = _dtype_code(x)
+    if y_perm is None:
+        y_perm = torch.empty((T * k, H), dtype=x.dtype, device=x.device)
+    need = int(load().moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, code))
+    if ws is None:
+        ws = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    _check(load().moe_grouped_ffn(_dev(x, x.dtype, "x"), _dev(perm_pair, torch.int32, "perm_pair"),
+                                  _dev(group_offsets, torch.int32, "group_offsets"), T, k, spr, H, I, code,
+                                  _dev(w13, x.dtype, "w13"), _dev(w2, x.dtype, "w2"),
+                                  _dev(y_perm, x.dtype, "y_perm"), _dev(ws, torch.uint8, "ws"), ws.numel(),
+                                  _stream()))
+    return y_perm
+
+
+def moe_unpermute(y_perm: torch.Tensor, pair_row: torch.Tensor, topk_w: torch.Tensor,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y_perm [T*k,H], pair_row [T,k] int32, topk_w [T,k] float32 -> out [T,H]."""
+    T, k = pair_row.shape
+    H = y_perm.shape[1]
+    code = _dtype_code(y_perm)
+    if out is None:
+        out = torch.empty((T, H), dtype=y_perm.dtype, device=y_perm.device)
+    _check(load().moe_unpermute(_dev(y_perm, y_perm.dtype, "y_perm"), _dev(pair_row, torch.int32, "pair_row"),
+                                _dev(topk_w, torch.float32, "topk_w"), T, k, H, code,
+                                _dev(out, y_perm.dtype, "out"), _stream()))
+    return out

@@ -1,0 +1,105 @@
+// Wavefront-level helpers shared by the gfx950 kernels (64-wide waves).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace metro {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+__device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) - 1ull; }
+
+// For the lanes with `valid`, the number of lower lanes holding the same key; `total`
+// receives the number of lanes holding it.  One ballot per distinct key in the wave.
+__device__ __forceinline__ int wave_rank_by_key(int key, bool valid, int& total) {
+    uint64_t todo = __ballot(valid);
+    int rank = 0;
+    total = 0;
+    const uint64_t below = lanes_below();
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const int leader_key = __builtin_amdgcn_readlane(key, leader);
+        const bool mine = valid && key == leader_key;
+        const uint64_t same = __ballot(mine);
+        if (mine) {
+            rank = __popcll(same & below);
+            total = __popcll(same);
+        }
+        todo &= ~same;
+    }
+    return rank;
+}
+
+// Stable occurrence numbering of n items by key, in item order, by one workgroup.
+//   hist: LDS, [n_waves][n_keys] ints.  tot: LDS, [n_keys] ints.
+// After pass 1 + prefix, hist[w][key] = items with that key owned by lower waves, tot[key] = all.
+// Each wave owns a contiguous run of 64-item chunks, so item order = (wave, chunk, lane).
+struct OrderedCounter {
+    int n, n_keys, chunks_per_wave;
+    int* hist;
+    int* tot;
+
+    __device__ __forceinline__ void init(int n_, int n_keys_, int* hist_, int* tot_) {
+        n = n_;
+        n_keys = n_keys_;
+        hist = hist_;
+        tot = tot_;
+        const int n_waves = blockDim.x >> 6;
+        const int chunks = (n + kWave - 1) / kWave;
+        chunks_per_wave = (chunks + n_waves - 1) / n_waves;
+        for (int i = threadIdx.x; i < n_waves * n_keys; i += blockDim.x) hist[i] = 0;
+    }
+
+    // key_of(item) -> key in [0, n_keys) or -1 to leave the item out.  Call between barriers.
+    template <typename KeyFn>
+    __device__ __forceinline__ void histogram(KeyFn key_of) {
+        int* mine = hist + wave_id() * n_keys;
+        const int first = wave_id() * chunks_per_wave;
+        for (int c = first; c < first + chunks_per_wave; ++c) {
+            const int item = c * kWave + lane_id();
+            if (item < n) {
+                const int key = key_of(item);
+                if (key >= 0) atomicAdd(&mine[key], 1);
+            }
+        }
+    }
+
+    // Turns per-wave counts into per-wave bases and totals.  Call between barriers.
+    __device__ __forceinline__ void prefix() {
+        const int n_waves = blockDim.x >> 6;
+        for (int key = threadIdx.x; key < n_keys; key += blockDim.x) {
+            int running = 0;
+            for (int w = 0; w < n_waves; ++w) {
+                const int c = hist[w * n_keys + key];
+                hist[w * n_keys + key] = running;
+                running += c;
+            }
+            tot[key] = running;
+        }
+    }
+
+    // emit(item, key, occ) for every item: occ = number of earlier items with the same key
+    // (key = -1: occ undefined).  Call between barriers.
+    template <typename KeyFn, typename EmitFn>
+    __device__ __forceinline__ void number(KeyFn key_of, EmitFn emit) {
+        int* mine = hist + wave_id() * n_keys;
+        const int first = wave_id() * chunks_per_wave;
+        for (int c = first; c < first + chunks_per_wave; ++c) {   // uniform per wave
+            const int item = c * kWave + lane_id();
+            const bool in_range = item < n;
+            const int key = in_range ? key_of(item) : -1;
+            const bool valid = key >= 0;
+            int total;
+            const int rank = wave_rank_by_key(key, valid, total);
+            int occ = 0;
+            if (valid) occ = mine[key] + rank;
+            // the wave executes in lockstep: every read of mine[] above precedes the update below
+            if (valid && rank == total - 1) mine[key] = occ + 1;
+            if (in_range) emit(item, key, occ);
+        }
+    }
+};
+
+}  // namespace metro
