@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the METRO hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic decode batch, inputs resident in HBM:
+    metro_route -> moe_permute (slowest rank) -> moe_grouped_ffn (plan, gate/up, down) -> moe_unpermute.
+The workload is the DeepSeek-V3-shaped decode layer (E=256, top-8, G=8 logical ranks, 36 slots per
+rank, T=1024, Zipf s=1.0, H=7168, I=2048, bf16) -- the shape the HBM-roofline target is stated on.
+"Slowest rank" = the rank whose expert FFN takes longest when measured (all G shares resident).
+
+Prints ONE JSON line: `value` = achieved algorithmic HBM GB/s of the slowest rank's expert FFN under
+METRO routing; the route latency, FFN times under both routers, the roofline of the dominant kernel
+(gate/up) and the CPU-oracle baseline ride along in the same object.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "METRO route µs/batch; slowest-rank expert-FFN µs & HBM GB/s (decode)"
+
+
+def algorithmic_bytes(active: int, P: int, H: int, I: int, elt: int = 2):
+    """Bytes the method itself must move for one rank: every activated slot's weights once, the
+    gathered activations, the intermediate act (written by gate/up, read by down) and y_perm."""
+    gate_up = active * 2 * I * H * elt + P * H * elt + P * I * elt + 4 * P
+    down = active * H * I * elt + P * I * elt + P * H * elt
+    return gate_up, down
+
+
+class HotPath:
+    """Device buffers and the step function for one (routing, rank) choice."""
+
+    def __init__(self, api, torch, w, d_ids, d_s2e, x, tw, shares, routing: str):
+        self.api, self.torch, self.w = api, torch, w
+        self.d_ids, self.d_s2e, self.x, self.tw, self.shares = d_ids, d_s2e, x, tw, shares
+        self.route_fn = api.metro_route if routing == "metro" else api.metro_route_token_balanced
+        dev = x.device
+        self.rb = api.route_buffers(1, w.T, w.k, w.N, w.G, dev)
+        self.pb = api.permute_buffers(w.T, w.k, w.spr, dev)
+        self.y = torch.empty((w.T * w.k, w.H), dtype=x.dtype, device=dev)
+        self.out = torch.empty((w.T, w.H), dtype=x.dtype, device=dev)
+        self.ws = torch.empty((api.moe_grouped_ffn_workspace_bytes(w.T, w.k, w.spr, w.H, w.I, x.dtype),),
+                              dtype=torch.uint8, device=dev)
+
+    def step(self, g: int, marks=None):
+        api, w = self.api, self.w
+        m = (lambda i: marks[i].record()) if marks is not None else (lambda i: None)
+        m(0)
+        self.route_fn(self.d_ids, self.d_s2e, w.N, w.G, w.spr, out=self.rb)
+        m(1)
+        api.moe_permute(self.rb["pair_slot"][0], g, w.spr, out=self.pb)
+        w13, w2 = self.shares[g]
+        api.moe_grouped_ffn_stages(self.x, self.pb["perm_pair"], self.pb["group_offsets"], w.k, w13, w2, self.y,
+                                   self.ws, between=lambda i: m(2 + i))
+        api.moe_unpermute(self.y, self.pb["pair_row"], self.tw, out=self.out)
+        m(6)
+
+    def ffn_only_us(self, g: int, iters: int = 3) -> float:
+        torch = self.torch
+        self.step(g)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+        tot = 0.0
+        for _ in range(iters):
+            self.step(g, ev)
+            torch.cuda.synchronize()
+            tot += ev[2].elapsed_time(ev[5])
+        return 1e3 * tot / iters
+
+    def timed(self, g: int, steps: int, warmup: int):
+        """W untimed + K timed steps; returns (ms_per_step, per-stage mean us)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(g)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            self.step(g, evs[s])
+        torch.cuda.synchronize()
+        wall_ms = 1e3 * (time.perf_counter() - t0)
+        names = ["route", "permute", "plan", "gate_up", "down", "unpermute"]
+        stage = {n: 1e3 * float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, n in enumerate(names)}
+        dev_ms = evs[0][0].elapsed_time(evs[-1][6])
+        return max(wall_ms, dev_ms) / steps, stage
+
+
+def routing_sweep(api, torch, W, quick: bool):
+    """Routing-only latency at the sweep shape (G=16, 58 layers per launch), us per batch."""
+    w = W.DSV3_SWEEP
+    rows = []
+    for T in ((1024,) if quick else W.SWEEP_T):
+        s2e, ids = W.routing_inputs_layers(w, T=T, s=1.0)
+        d_ids, d_s2e = torch.from_numpy(ids).cuda(), torch.from_numpy(s2e).cuda()
+        ref = {}
+        for name, fn in (("metro", api.metro_route), ("token_balanced", api.metro_route_token_balanced)):
+            buf = api.route_buffers(w.layers, T, w.k, w.N, w.G, "cuda")
+            one = api.route_buffers(1, T, w.k, w.N, w.G, "cuda")
+            for _ in range(5):
+                fn(d_ids, d_s2e, w.N, w.G, w.spr, out=buf)
+                fn(d_ids[:1], d_s2e[:1], w.N, w.G, w.spr, out=one)
+            a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            n = 50
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(n):
+                fn(d_ids, d_s2e, w.N, w.G, w.spr, out=buf)
+            b.record()
+            for _ in range(n):
+                fn(d_ids[:1], d_s2e[:1], w.N, w.G, w.spr, out=one)
+            c.record()
+            torch.cuda.synchronize()
+            ref[name] = dict(us_per_batch_58_layers_per_launch=round(1e3 * a.elapsed_time(b) / n / w.layers, 3),
+                             us_per_single_layer_launch=round(1e3 * b.elapsed_time(c) / n, 3),
+                             max_activated_per_rank_mean=round(float(buf["rank_active"].max(dim=1).values.float().mean()), 3))
+        rows.append(dict(T=T, s=1.0, **ref))
+    return rows
+
+
+def cpu_baseline(oracle, W, w, ids, s2e, host_x, host_w13, host_w2, perm, ffn_bytes, budget_s: float):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample."""
+    t0 = time.perf_counter()
+    n_route = 0
+    while time.perf_counter() - t0 < 1.0:
+        oracle.route_metro(ids, s2e, w.N, w.G, w.spr)
+        n_route += 1
+    route_us = 1e6 * (time.perf_counter() - t0) / n_route
+    P = perm["n_pairs"]
+    threads = oracle.num_threads()
+    rng = np.random.default_rng(0)
+    probe = np.sort(rng.choice(P, size=min(P, threads), replace=False))
+    t0 = time.perf_counter()
+    oracle.ffn(host_x, perm["perm_pair"], perm["group_offsets"], w.k, host_w13, host_w2, rows=probe)
+    per_batch = time.perf_counter() - t0
+    n = int(min(P, max(threads, threads * int(budget_s / max(per_batch, 1e-3)))))
+    rows = np.sort(rng.choice(P, size=n, replace=False))
+    t0 = time.perf_counter()
+    oracle.ffn(host_x, perm["perm_pair"], perm["group_offsets"], w.k, host_w13, host_w2, rows=rows)
+    dt = time.perf_counter() - t0
+    full_s = dt * P / n
+    return dict(value=round(ffn_bytes / full_s / 1e9, 4), unit="GB/s", cores=threads, kind="oracle",
+                sample=f"{n} of the slowest rank's {P} rows (all columns) in {dt:.1f} s, scaled to {P} rows; "
+                       f"routing oracle: 1 core, {n_route} batches",
+                ffn_us_extrapolated=round(1e6 * full_s, 1), route_us_per_batch=round(route_us, 2))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="deepseek_v3_decode")
+    ap.add_argument("--rank", type=int, default=-1, help="pin the measured rank (skips the per-rank search)")
+    ap.add_argument("--only-metro", action="store_true", help="skip the token-balanced comparison and the sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle FFN work")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference reading for rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the G expert-parallel ranks are logical); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2512_09277_amd import api
+    from paper_2512_09277_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    api.load()
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    if w.H == 0:
+        print("that workload has no FFN shape", file=sys.stderr)
+        return 2
+
+    _, s2e, ids = W.routing_inputs(w)
+    d_ids = torch.from_numpy(ids).cuda().unsqueeze(0)
+    d_s2e = torch.from_numpy(s2e).cuda().unsqueeze(0)
+    x = W.device_activations(w, "cuda")
+    tw = torch.from_numpy(W.gating_weights(w.T, w.k, w.seed(0, 4))).cuda()
+    lw13, lw2 = W.device_expert_weights(w, "cuda")
+    ranks = range(w.G) if args.rank < 0 else [args.rank]
+    shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr), W.device_rank_share(lw2, s2e, g, w.spr)) for g in ranks}
+    del lw13, lw2
+    torch.cuda.synchronize()
+
+    if args.calibration_copy:
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    result = {}
+    for routing in (("metro",) if args.only_metro else ("metro", "token_balanced")):
+        hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
+        per_rank = {g: hp.ffn_only_us(g) for g in ranks}
+        g = max(per_rank, key=per_rank.get)
+        ms_per_step, stage = hp.timed(g, args.steps, args.warmup)
+        assert int(hp.rb["err_flag"].item()) == 0
+        active = int(hp.rb["rank_active"][0, g].item())
+        P = int(hp.pb["n_pairs"].item())
+        gu_b, dn_b = algorithmic_bytes(active, P, w.H, w.I)
+        ffn_us = stage["plan"] + stage["gate_up"] + stage["down"]
+        result[routing] = dict(rank=g, ms_per_step=ms_per_step, stage_us={k: round(v, 2) for k, v in stage.items()},
+                               ffn_us=ffn_us, active=active, pairs=P, bytes=(gu_b, dn_b),
+                               lam=int(hp.rb["rank_active"].max().item()),
+                               per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank.items()},
+                               perm={k: v.cpu().numpy() for k, v in hp.pb.items()})
+    me = result["metro"]
+    gu_b, dn_b = me["bytes"]
+    ffn_gbs = (gu_b + dn_b) / (me["ffn_us"] * 1e-6) / 1e9
+    gu_gbs = gu_b / (me["stage_us"]["gate_up"] * 1e-6) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "ffn_gate_up_dsv3_traffic.json")
+    if os.path.exists(tpath) and w.name == "deepseek_v3_decode":
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+
+    line = {
+        "metric": METRIC, "value": round(ffn_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(me["ms_per_step"], 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "E": w.N, "top_k": w.k, "G_logical_ranks": w.G, "slots_per_rank": w.spr,
+                   "T": w.T, "zipf_s": w.s, "H": w.H, "I": w.I, "measured_rank": me["rank"], "routing": "metro"},
+        "route_us_per_batch": me["stage_us"]["route"],
+        "ffn_us": {"metro": round(me["ffn_us"], 1)},
+        "max_activated_per_rank": {"metro": me["lam"]},
+        "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
+        "stage_us": me["stage_us"],
+        "per_rank_ffn_us": {"metro": me["per_rank_ffn_us"]},
+        "roofline": {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(gu_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "algorithmic_bytes_per_launch": gu_b,
+                     "down_kernel": {"achieved": round(dn_b / (me["stage_us"]["down"] * 1e-6) / 1e9, 1),
+                                     "algorithmic_bytes_per_launch": dn_b}},
+    }
+    if "token_balanced" in result:
+        tb = result["token_balanced"]
+        line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)
+        line["max_activated_per_rank"]["token_balanced"] = tb["lam"]
+        line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
+        line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
+        line["ms_per_step_token_balanced"] = round(tb["ms_per_step"], 4)
+        line["routing_sweep"] = routing_sweep(api, torch, W, quick=False)
+    if not args.no_cpu_baseline:
+        from oracle import metro_oracle as oracle
+
+        oracle.build()
+        g = me["rank"]
+        host = lambda t: t.cpu().view(torch.int16).numpy().view(np.uint16)
+        perm = dict(me["perm"])
+        perm["n_pairs"] = int(perm["n_pairs"][0])
+        line["cpu_baseline"] = cpu_baseline(oracle, W, w, ids, s2e, host(x), host(shares[g][0]), host(shares[g][1]),
+                                            perm, gu_b + dn_b, args.cpu_budget)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -116,6 +116,22 @@ int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* grou
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The three stages of moe_grouped_ffn as separate calls, in the order plan -> gate_up -> down, on
+ * the same workspace and stream (moe_grouped_ffn is exactly that sequence).  They exist so that a
+ * caller can put events between the stages or overlap other work; arguments as above.
+ *   plan     turns group_offsets into the work list of the two kernels
+ *   gate_up  act = silu(x . w13[gate]^T) * (x . w13[up]^T), kept in the workspace
+ *   down     y_perm = act . w2^T
+ */
+int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype, void* ws,
+                         size_t ws_bytes, void* stream);
+int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
+                            int spr, int H, int I, int dtype, const void* w13, void* ws, size_t ws_bytes,
+                            void* stream);
+int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
+                         const void* w2, void* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * moe_unpermute -- the rank's share of the combine step (Sec. 2.2): for every token,
  *     out[t] = sum over j ascending of topk_w[t,j] * y_perm[pair_row[t,j]]   (pairs served here),
  * accumulated in fp32; tokens with no pair on this rank get zeros.

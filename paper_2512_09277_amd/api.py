@@ -21,7 +21,8 @@ FLAG_BAD_ID, FLAG_NO_REPLICA, FLAG_BAD_PLACEMENT = 1, 2, 4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ("metro_status_string", "metro_route", "metro_route_token_balanced", "moe_permute",
-           "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_unpermute")
+           "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_plan", "moe_grouped_ffn_gate_up",
+           "moe_grouped_ffn_down", "moe_unpermute")
 
 
 class MetroError(RuntimeError):
@@ -51,6 +52,12 @@ def load() -> ctypes.CDLL:
         lib.moe_grouped_ffn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
         lib.moe_grouped_ffn.restype = ci
         lib.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        lib.moe_grouped_ffn_plan.restype = ci
+        lib.moe_grouped_ffn_plan.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
+        lib.moe_grouped_ffn_gate_up.restype = ci
+        lib.moe_grouped_ffn_gate_up.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, sz, vp]
+        lib.moe_grouped_ffn_down.restype = ci
+        lib.moe_grouped_ffn_down.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
         lib.moe_unpermute.restype = ci
         lib.moe_unpermute.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
         _lib = lib
@@ -173,6 +180,29 @@ def moe_grouped_ffn(x: torch.Tensor, perm_pair: torch.Tensor, group_offsets: tor
                                   _dev(w13, x.dtype, "w13"), _dev(w2, x.dtype, "w2"),
                                   _dev(y_perm, x.dtype, "y_perm"), _dev(ws, torch.uint8, "ws"), ws.numel(),
                                   _stream()))
+    return y_perm
+
+
+def moe_grouped_ffn_stages(x, perm_pair, group_offsets, k: int, w13, w2, y_perm, ws, between=None):
+    """moe_grouped_ffn as its three stage calls; `between(i)` (i = 0..3) is called before, between and
+    after the stages, e.g. to record events on the current stream."""
+    T, H = x.shape
+    spr, two_i, _ = w13.shape
+    I = two_i // 2
+    code = _dtype_code(x)
+    lib = load()
+    go = _dev(group_offsets, torch.int32, "group_offsets")
+    wsp, wsn = _dev(ws, torch.uint8, "ws"), ws.numel()
+    mark = between if between is not None else (lambda i: None)
+    mark(0)
+    _check(lib.moe_grouped_ffn_plan(go, T, k, spr, H, I, code, wsp, wsn, _stream()))
+    mark(1)
+    _check(lib.moe_grouped_ffn_gate_up(_dev(x, x.dtype, "x"), _dev(perm_pair, torch.int32, "perm_pair"), go, T, k,
+                                       spr, H, I, code, _dev(w13, x.dtype, "w13"), wsp, wsn, _stream()))
+    mark(2)
+    _check(lib.moe_grouped_ffn_down(go, T, k, spr, H, I, code, _dev(w2, x.dtype, "w2"),
+                                    _dev(y_perm, x.dtype, "y_perm"), wsp, wsn, _stream()))
+    mark(3)
     return y_perm
 
 

@@ -1,17 +1,23 @@
 // moe_grouped_ffn for gfx950: SwiGLU expert FFN over one rank's per-slot token lists.
 //
 // Decode is HBM-bound: runtime follows the bytes of the activated experts' weights (Sec. 3.2 of
-// arxiv 2512.09277), so the kernels are built around streaming every activated weight row from
-// HBM exactly once with 128-bit loads straight into the matrix-core operand layout, while the
-// (small, heavily reused) activations are staged through LDS:
-//   plan     : one wave turns group_offsets into a list of work tiles (slot, first row, rows<=128),
-//              heaviest first, so that the few wide groups are spread over the chip early;
-//   gate/up  : tile x 64 intermediate columns per workgroup; each wave owns 16 gate rows and the
-//              16 matching up rows, so silu(gate)*up is formed in registers and written as bf16;
-//   down     : tile x 128 output columns per workgroup, same structure over K = I.
+// arxiv 2512.09277).  Every activated weight row is streamed from HBM once, with 128-bit loads that
+// land directly in the matrix-core operand layout (16 rows x 64 contiguous bytes per instruction);
+// the small, heavily reused activations are staged through LDS.  Work is cut into tiles of one
+// slot's rows:
+//   stream tiles (<= 32 rows, the bulk of the bytes): per wave 2 x 16 weight rows, K steps of 128,
+//       loads issued two steps ahead so that ~128 KB per CU are in flight at 2 waves per SIMD;
+//   wide tiles (33..128 rows, the few popular experts): per wave 4 x 16 weight rows, K steps of 64,
+//       so that each activation fragment read from LDS feeds four MFMAs and the matrix cores,
+//       not LDS, bound the tile; they are listed first so that they spread over the chip early.
+//   gate/up: a wave owns gate rows and the matching up rows, so silu(gate)*up is formed in
+//            registers and written once as bf16;   down: same structure over K = I.
 // A slot with no rows produces no tile and its weights are never touched.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
+#include <utility>
 
 #include "device_utils.h"
 #include "metro.h"
@@ -24,13 +30,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBK = 128;                    // K elements per pipeline step
-constexpr int kLdsRow = kBK * 2 + 16;       // bytes per staged activation row (+16: bank spread)
-constexpr int kMaxMT = 8;                   // 16-row sub-tiles per work tile
-constexpr int kTileRows = kMaxMT * 16;      // 128
-constexpr int kLdsBytes = 2 * kTileRows * kLdsRow;
 constexpr int kThreads = 256;
 constexpr int kMaxSpr = 64;
+constexpr int kWideRows = 128;              // rows of a full wide tile
+constexpr int kStreamRows = 32;             // a remainder of at most this many rows is a stream tile
 constexpr size_t kPlanBytes = 256;          // header before the tile list
 
 struct Tile {
@@ -38,12 +41,15 @@ struct Tile {
 };
 
 struct PlanHeader {
-    int n_tiles;
+    int n_wide, n_stream;                   // tiles[0, n_wide) wide, then n_stream stream tiles
 };
 
-__host__ __device__ inline int max_tiles(int cap, int spr) { return spr + cap / kTileRows; }
+__host__ __device__ inline int max_tiles(int cap, int spr) { return spr + cap / kWideRows; }
 
 // ------------------------------------------------------------------------------------------ plan
+// One wave, lane = local slot.  A slot of m rows gives m / 128 full wide tiles and one tile for the
+// remainder (wide if > 32 rows, else stream).  Order: full wide tiles, partial wide tiles by rows
+// descending, stream tiles by rows descending.
 __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ group_offsets, int spr, int cap,
                                                      int tile_cap, PlanHeader* __restrict__ hdr,
                                                      Tile* __restrict__ tiles) {
@@ -53,7 +59,7 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         begin = min(max(group_offsets[l], 0), cap);
         m = min(max(group_offsets[l + 1], begin), cap) - begin;
     }
-    const int full = m / kTileRows, part = m % kTileRows;
+    const int full = m / kWideRows, part = m % kWideRows;
     int incl = full;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -61,16 +67,21 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         if (l >= d) incl += up;
     }
     const int n_full = __shfl(incl, kWave - 1);
-    int rank = 0;                               // partial tiles: more rows first, then lower slot
+    int rank = 0;                               // remainders: more rows first, then lower slot
     for (int j = 0; j < kWave; ++j) {
         const int pj = __shfl(part, j);
         rank += (pj > part || (pj == part && j < l)) ? 1 : 0;
     }
+    const int n_part_wide = __popcll(__ballot(part > kStreamRows));
     const int n_part = __popcll(__ballot(part > 0));
     for (int f = 0; f < full; ++f)
-        if (incl - full + f < tile_cap) tiles[incl - full + f] = Tile{l, begin + f * kTileRows, kTileRows, 0};
-    if (part > 0 && n_full + rank < tile_cap) tiles[n_full + rank] = Tile{l, begin + full * kTileRows, part, 0};
-    if (l == 0) hdr->n_tiles = min(n_full + n_part, tile_cap);
+        if (incl - full + f < tile_cap) tiles[incl - full + f] = Tile{l, begin + f * kWideRows, kWideRows, 0};
+    if (part > 0 && n_full + rank < tile_cap) tiles[n_full + rank] = Tile{l, begin + full * kWideRows, part, 0};
+    if (l == 0) {
+        const int n_wide = min(n_full + n_part_wide, tile_cap);
+        hdr->n_wide = n_wide;
+        hdr->n_stream = min(n_full + n_part, tile_cap) - n_wide;
+    }
 }
 
 // ------------------------------------------------------------------------------------------ MFMA path
@@ -81,7 +92,8 @@ struct FfnArgs {
     __bf16* dst;              // gate/up: act[cap,I]; down: y_perm[cap,H]
     const PlanHeader* hdr;
     const Tile* tiles;
-    int T, k, H, I, n_ntiles;
+    int T, k, H, I;
+    int nt_wide, nt_stream;   // column tiles per wide / stream tile
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -93,150 +105,206 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 
-template <int MT>
-struct Accum {
-    floatx4 a[MT], b[MT];
-};
-
-// One K step: issue the next step's loads, run this step's MFMAs, park the next activations in LDS.
-template <int MT>
-__device__ __forceinline__ void k_step(const u32x4 (&w_cur)[8], u32x4 (&w_nxt)[8], const u32x4* pa0, const u32x4* pa1,
-                                       const u32x4* (&px)[MT], int step, int n_steps, int mt_count,
-                                       const char* lds_cur, char* lds_nxt, int rd_off, int wr_off,
-                                       Accum<MT>& acc) {
-    const bool more = step + 1 < n_steps;
-    u32x4 xr[MT];
-    if (more) {
-        const int o = (step + 1) * (kBK * 2 / 16);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            w_nxt[j] = pa0[o + j];
-            w_nxt[4 + j] = pa1[o + j];
-        }
-#pragma unroll
-        for (int pz = 0; pz < MT; ++pz) xr[pz] = px[pz][o];
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        if (mt < mt_count) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bf16x8 xb = *reinterpret_cast<const bf16x8*>(lds_cur + rd_off + mt * 16 * kLdsRow + j * 16);
-                acc.a[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w_cur[j]), xb,
-                                                                    acc.a[mt], 0, 0, 0);
-                acc.b[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w_cur[4 + j]), xb,
-                                                                    acc.b[mt], 0, 0, 0);
-            }
-        }
-    }
-    if (more) {
-#pragma unroll
-        for (int pz = 0; pz < MT; ++pz) *reinterpret_cast<u32x4*>(lds_nxt + wr_off + pz * 16 * kLdsRow) = xr[pz];
-    }
-    __syncthreads();
-}
-
-template <bool kGateUp, int MT>
-__device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const int nt, char* lds) {
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int r16 = lane & 15, q = lane >> 4;
+// D[i][j] of block b, sub-tile mt: i = output column 4*q + v of the block, j = tile row r16.
+template <bool kGateUp, int NB, int MT>
+__device__ __forceinline__ void store_tile(const FfnArgs& a, const Tile& t, const floatx4 (&acc)[NB][MT], int col0,
+                                           int n_out, int mt_count, int r16, int q) {
     const int H = a.H, I = a.I;
-    const int K = kGateUp ? H : I;
-    const int n_steps = K / kBK;
-    const int mt_count = (t.rows + 15) >> 4;
-
-    // weight rows of this wave: two blocks of 16 rows; lane (r16, q) streams 64 contiguous bytes
-    // of row r16 per step (k = step*128 + q*32 .. +32), i.e. four MFMA operands.
-    int row_a0, row_a1;
-    size_t slot_elems;
-    if (kGateUp) {
-        row_a0 = nt * 64 + wv * 16 + r16;
-        row_a1 = row_a0 + I;
-        slot_elems = (size_t)2 * I * H;
-    } else {
-        row_a0 = nt * 128 + wv * 32 + r16;
-        row_a1 = row_a0 + 16;
-        slot_elems = (size_t)H * I;
-    }
-    const __bf16* wbase = a.w + (size_t)t.slot * slot_elems;
-    const u32x4* pa0 = reinterpret_cast<const u32x4*>(wbase + (size_t)row_a0 * K + q * 32);
-    const u32x4* pa1 = reinterpret_cast<const u32x4*>(wbase + (size_t)row_a1 * K + q * 32);
-
-    // activation staging: thread (frow, fchunk) copies 16 bytes of row pz*16+frow per step.
-    const int frow = tid >> 4, fchunk = tid & 15;
-    const u32x4* px[MT];
-#pragma unroll
-    for (int pz = 0; pz < MT; ++pz) {
-        int row = pz * 16 + frow;
-        row = row < t.rows ? row : t.rows - 1;              // rows past the tile repeat its last row
-        const size_t src_row = kGateUp ? (size_t)min(max(a.perm_pair[t.row0 + row] / a.k, 0), a.T - 1)
-                                       : (size_t)(t.row0 + row);
-        px[pz] = reinterpret_cast<const u32x4*>(a.src + src_row * K) + fchunk;
-    }
-    const int wr_off = frow * kLdsRow + fchunk * 16;
-    const int rd_off = r16 * kLdsRow + q * 64;
-    char* lds0 = lds;
-    char* lds1 = lds + kTileRows * kLdsRow;
-
-    Accum<MT> acc;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        acc.a[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-        acc.b[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    u32x4 w0[8], w1[8];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        w0[j] = pa0[j];
-        w0[4 + j] = pa1[j];
-    }
-#pragma unroll
-    for (int pz = 0; pz < MT; ++pz) *reinterpret_cast<u32x4*>(lds0 + wr_off + pz * 16 * kLdsRow) = px[pz][0];
-    __syncthreads();
-
-    for (int s = 0; s < n_steps; s += 2) {
-        k_step<MT>(w0, w1, pa0, pa1, px, s, n_steps, mt_count, lds0, lds1, rd_off, wr_off, acc);
-        if (s + 1 < n_steps)
-            k_step<MT>(w1, w0, pa0, pa1, px, s + 1, n_steps, mt_count, lds1, lds0, rd_off, wr_off, acc);
-    }
-
-    // D[i][j]: i = weight row 4*q + v of the 16-row block, j = tile row r16.
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int row = mt * 16 + r16;
         if (mt < mt_count && row < t.rows) {
             if (kGateUp) {
-                const floatx4 g = acc.a[mt], u = acc.b[mt];
-                u32x2 o;
-                o.x = pack_bf16x2(silu(g[0]) * u[0], silu(g[1]) * u[1]);
-                o.y = pack_bf16x2(silu(g[2]) * u[2], silu(g[3]) * u[3]);
-                *reinterpret_cast<u32x2*>(a.dst + (size_t)(t.row0 + row) * I + nt * 64 + wv * 16 + q * 4) = o;
+#pragma unroll
+                for (int b = 0; b < NB / 2; ++b) {
+                    const int col = col0 + b * 16;
+                    if (col < n_out) {
+                        const floatx4 g = acc[b][mt], u = acc[b + NB / 2][mt];
+                        u32x2 o;
+                        o.x = pack_bf16x2(silu(g[0]) * u[0], silu(g[1]) * u[1]);
+                        o.y = pack_bf16x2(silu(g[2]) * u[2], silu(g[3]) * u[3]);
+                        *reinterpret_cast<u32x2*>(a.dst + (size_t)(t.row0 + row) * I + col + q * 4) = o;
+                    }
+                }
             } else {
-                __bf16* out = a.dst + (size_t)(t.row0 + row) * H + nt * 128 + wv * 32 + q * 4;
-                u32x2 o;
-                o.x = pack_bf16x2(acc.a[mt][0], acc.a[mt][1]);
-                o.y = pack_bf16x2(acc.a[mt][2], acc.a[mt][3]);
-                *reinterpret_cast<u32x2*>(out) = o;
-                o.x = pack_bf16x2(acc.b[mt][0], acc.b[mt][1]);
-                o.y = pack_bf16x2(acc.b[mt][2], acc.b[mt][3]);
-                *reinterpret_cast<u32x2*>(out + 16) = o;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const int col = col0 + b * 16;
+                    if (col < n_out) {
+                        u32x2 o;
+                        o.x = pack_bf16x2(acc[b][mt][0], acc[b][mt][1]);
+                        o.y = pack_bf16x2(acc[b][mt][2], acc[b][mt][3]);
+                        *reinterpret_cast<u32x2*>(a.dst + (size_t)(t.row0 + row) * H + col + q * 4) = o;
+                    }
+                }
             }
         }
     }
 }
 
+// do_step(U, s) for U = 0..n-1 with compile-time U (buffer indices), s = s0 + U.
+template <int... Us, typename F>
+__device__ __forceinline__ void run_steps(std::integer_sequence<int, Us...>, F& f, int s0) {
+    (f(std::integral_constant<int, Us>{}, s0 + Us), ...);
+}
+template <int... Us, typename F>
+__device__ __forceinline__ void run_steps_tail(std::integer_sequence<int, Us...>, F& f, int s0, int n_steps) {
+    ((s0 + Us < n_steps ? f(std::integral_constant<int, Us>{}, s0 + Us) : void()), ...);
+}
+
+// One tile x one column tile.
+//   NB    16-row weight blocks per wave (gate/up: NB/2 gate blocks + the matching up blocks)
+//   MT    16-row activation sub-tiles (tile rows <= 16*MT)
+//   BK    K elements per step;  DEPTH  steps the loads run ahead
+// Lane (r16, q) of a wave supplies, for MFMA j of a step, the 8 elements k = j*32 + q*8 .. +8 of
+// weight row r16 (A operand) and of tile row r16 (B operand): one load instruction reads 64
+// contiguous bytes of each of 16 rows.  D[i][j]: i = weight row 4*q + v, j = tile row r16.
+template <bool kGateUp, int NB, int MT, int BK, int DEPTH>
+__device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const int nt, char* lds) {
+    constexpr int NJ = BK / 32;                 // MFMAs per block per step
+    constexpr int NW = DEPTH + 1;               // weight register buffers
+    constexpr int kLdsRow = BK * 2 + 16;        // bytes per staged row (+16 spreads the banks)
+    constexpr int kChunks = BK * 2 / 16;        // 16-byte chunks per staged row
+    constexpr int kRowsPerPass = kThreads / kChunks;
+    constexpr int NP = (MT * 16 + kRowsPerPass - 1) / kRowsPerPass;   // staging loads per thread
+    constexpr int kPeriod = (DEPTH == 1) ? 2 : (DEPTH == 2) ? 6 : 12; // lcm(NW, DEPTH, 2)
+    static_assert(DEPTH >= 1 && DEPTH <= 3, "prefetch distance");
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, q = lane >> 4;
+    const int H = a.H, I = a.I;
+    const int K = kGateUp ? H : I;
+    const int n_steps = K / BK;
+    const int mt_count = (t.rows + 15) >> 4;
+    const int n_out = kGateUp ? I : H;          // output columns of this stage
+    const int cols_per_wave = kGateUp ? NB * 8 : NB * 16;
+    const int col0 = nt * 4 * cols_per_wave + wv * cols_per_wave;     // first output column of the wave
+
+    // weight row of block b: gate/up pairs block b (gate) with block b + NB/2 (up)
+    const __bf16* wbase = a.w + (size_t)t.slot * (kGateUp ? (size_t)2 * I * H : (size_t)H * I);
+    const char* pw[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        int col = kGateUp ? col0 + (b % (NB / 2)) * 16 : col0 + b * 16;
+        col = col < n_out ? col : n_out - 16;   // a block past the last column repeats the last block
+        const int row = (kGateUp && b >= NB / 2) ? I + col + r16 : col + r16;
+        pw[b] = reinterpret_cast<const char*>(wbase + (size_t)row * K) + q * 16;
+    }
+
+    // activation staging: thread (frow, fchunk) copies 16 bytes of rows frow, frow + kRowsPerPass, ...
+    const int frow = tid / kChunks, fchunk = tid % kChunks;
+    const char* px[NP];
+#pragma unroll
+    for (int pz = 0; pz < NP; ++pz) {
+        int row = pz * kRowsPerPass + frow;
+        row = row < t.rows ? row : t.rows - 1;  // rows past the tile repeat its last row
+        const size_t src_row = kGateUp ? (size_t)min(max(a.perm_pair[t.row0 + row] / a.k, 0), a.T - 1)
+                                       : (size_t)(t.row0 + row);
+        px[pz] = reinterpret_cast<const char*>(a.src + src_row * K) + fchunk * 16;
+    }
+    const int wr_off = frow * kLdsRow + fchunk * 16;
+    const int rd_off = r16 * kLdsRow + q * 16;
+    constexpr int kLdsBuf = MT * 16 * kLdsRow;
+
+    floatx4 acc[NB][MT];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[b][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 w[NW][NB * NJ];
+    u32x4 xr[DEPTH][NP];
+
+    auto load_w = [&](int buf, int step) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                w[buf][b * NJ + j] = *reinterpret_cast<const u32x4*>(pw[b] + (size_t)step * (BK * 2) + j * 64);
+    };
+    auto load_x = [&](int set, int step) {
+#pragma unroll
+        for (int pz = 0; pz < NP; ++pz)
+            if (NP * kRowsPerPass <= MT * 16 || pz * kRowsPerPass + frow < MT * 16)
+                xr[set][pz] = *reinterpret_cast<const u32x4*>(px[pz] + (size_t)step * (BK * 2));
+    };
+    auto park_x = [&](int set, int buf) {
+#pragma unroll
+        for (int pz = 0; pz < NP; ++pz)
+            if (NP * kRowsPerPass <= MT * 16 || pz * kRowsPerPass + frow < MT * 16)
+                *reinterpret_cast<u32x4*>(lds + buf * kLdsBuf + wr_off + pz * kRowsPerPass * kLdsRow) = xr[set][pz];
+    };
+
+    // Every load below is unconditional (past the last step the index is clamped, which re-reads
+    // the last step): the compiler can then count outstanding loads exactly and waits only for
+    // the ones a step consumes, instead of draining the queue at every branch join.
+    const int last = n_steps - 1;
+    load_x(0, 0);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        if (d >= 1) load_x(d % DEPTH, min(d, last));
+        load_w(d, min(d, last));
+    }
+    park_x(0, 0);
+    __syncthreads();
+
+    // One K step with compile-time buffer indices u (step s = u mod kPeriod).
+    auto do_step = [&](auto U, int s) {
+        constexpr int u = decltype(U)::value;
+        // Loads retire in issue order: the activations go first so that waiting for them (to park
+        // them one step later) never waits for the younger weight loads.
+        const int ps = min(s + DEPTH, last);
+        load_x(u % DEPTH, ps);
+        load_w((u + DEPTH) % NW, ps);
+        const char* cur = lds + (u % 2) * kLdsBuf + rd_off;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (mt < mt_count) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const bf16x8 xb = *reinterpret_cast<const bf16x8*>(cur + mt * 16 * kLdsRow + j * 64);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        acc[b][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, w[u % NW][b * NJ + j]), xb, acc[b][mt], 0, 0, 0);
+                }
+            }
+        }
+        // activations of step s+1 were loaded DEPTH-1 steps ago (set (s+1) % DEPTH)
+        park_x((u + 1) % DEPTH, (u + 1) % 2);
+        __syncthreads();
+    };
+
+    int s0 = 0;
+    for (; s0 + kPeriod <= n_steps; s0 += kPeriod) run_steps(std::make_integer_sequence<int, kPeriod>{}, do_step, s0);
+    run_steps_tail(std::make_integer_sequence<int, kPeriod - 1>{}, do_step, s0, n_steps);
+
+    store_tile<kGateUp, NB, MT>(a, t, acc, col0, n_out, mt_count, r16, q);
+}
+
+constexpr int kLdsStream = 2 * 32 * (128 * 2 + 16);
+constexpr int kLdsWide = 2 * 128 * (64 * 2 + 16);
+constexpr int kLdsBytes = kLdsWide > kLdsStream ? kLdsWide : kLdsStream;
+
 template <bool kGateUp>
 __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int tile_idx = blockIdx.x / a.n_ntiles;
-    const int nt = blockIdx.x - tile_idx * a.n_ntiles;
-    if (tile_idx >= a.hdr->n_tiles) return;              // uniform: the whole workgroup leaves
-    const Tile t = a.tiles[tile_idx];
-    if (t.rows <= 16) ffn_tile<kGateUp, 1>(a, t, nt, lds);
-    else if (t.rows <= 32) ffn_tile<kGateUp, 2>(a, t, nt, lds);
-    else if (t.rows <= 64) ffn_tile<kGateUp, 4>(a, t, nt, lds);
-    else ffn_tile<kGateUp, 8>(a, t, nt, lds);
+    const int n_wide = a.hdr->n_wide, n_stream = a.hdr->n_stream;
+    // Work items = (tile, column tile), wide tiles first: a wide workgroup lives several times longer
+    // than a stream one, so it has to start early for the stream items to fill in around it.
+    int id = blockIdx.x;                                     // everything below is uniform per workgroup
+    const int wide_items = n_wide * a.nt_wide;
+    if (id < wide_items) {
+        const int ti = id / a.nt_wide;
+        ffn_tile<kGateUp, 4, 8, 64, 1>(a, a.tiles[ti], id - ti * a.nt_wide, lds);
+        return;
+    }
+    id -= wide_items;
+    const int ti = id / a.nt_stream;
+    if (ti >= n_stream) return;
+    const Tile t = a.tiles[n_wide + ti];
+    if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, id - ti * a.nt_stream, lds);
+    else ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, id - ti * a.nt_stream, lds);
 }
 
 // ------------------------------------------------------------------------------------------ general path
@@ -320,16 +388,49 @@ inline bool mfma_shape(int H, int I, int dtype) {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-template <typename Elem>
-int launch_general(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k, int spr,
-                   int H, int I, const void* w13, const void* w2, void* y, float* act, hipStream_t st) {
-    const int per = kThreads / kWave, cap = T * k;
-    hipLaunchKernelGGL(general_gate_up_kernel<Elem>, dim3(cap, (I + per - 1) / per), dim3(kThreads), 0, st,
-                       (const Elem*)x, perm_pair, group_offsets, T, k, spr, H, I, (const Elem*)w13, act);
-    hipLaunchKernelGGL(general_down_kernel<Elem>, dim3(cap, (H + per - 1) / per), dim3(kThreads), 0, st, act,
-                       group_offsets, spr, H, I, (const Elem*)w2, (Elem*)y);
-    return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
+// Workspace layout shared by the three stages: [header 256 B][tile list][act].
+struct Workspace {
+    PlanHeader* hdr;
+    Tile* tiles;
+    char* act;
+    int tile_cap;
+};
+
+inline Workspace carve(void* ws, int cap, int spr) {
+    Workspace w;
+    char* base = (char*)ws;
+    w.hdr = (PlanHeader*)base;
+    w.tiles = (Tile*)(base + kPlanBytes);
+    w.tile_cap = max_tiles(cap, spr);
+    w.act = base + kPlanBytes + align256(sizeof(Tile) * (size_t)w.tile_cap);
+    return w;
 }
+
+int check_common(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype, const void* ws,
+                 size_t ws_bytes) {
+    if (!group_offsets || !ws) return METRO_ERR_INVALID_ARG;
+    if (T < 0 || k < 1 || spr < 1 || H < 1 || I < 1) return METRO_ERR_INVALID_ARG;
+    if (dtype != METRO_DTYPE_BF16 && dtype != METRO_DTYPE_F32) return METRO_ERR_UNSUPPORTED;
+    if (spr > kMaxSpr || (int64_t)T * k >= (1 << 24)) return METRO_ERR_UNSUPPORTED;
+    if (((uintptr_t)ws & 255) != 0) return METRO_ERR_INVALID_ARG;
+    if (ws_bytes < moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, dtype)) return METRO_ERR_WORKSPACE;
+    return METRO_OK;
+}
+
+int enable_large_lds() {                            // opt in to > 64 KB of dynamic LDS, once
+    static bool done = false;
+    if (!done) {
+        if (hipFuncSetAttribute((const void*)ffn_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute((const void*)ffn_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes) != hipSuccess)
+            return METRO_ERR_HIP;
+        done = true;
+    }
+    return METRO_OK;
+}
+
+inline int launched() { return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP; }
 
 }  // namespace
 }  // namespace metro
@@ -343,58 +444,101 @@ extern "C" size_t moe_grouped_ffn_workspace_bytes(int T, int k, int spr, int H, 
     return plan + act + 256;
 }
 
-extern "C" int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
-                               int spr, int H, int I, int dtype, const void* w13, const void* w2, void* y_perm,
-                               void* ws, size_t ws_bytes, void* stream) {
+extern "C" int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
+                                    void* ws, size_t ws_bytes, void* stream) {
     using namespace metro;
-    if (!x || !perm_pair || !group_offsets || !w13 || !w2 || !y_perm || !ws) return METRO_ERR_INVALID_ARG;
-    if (T < 0 || k < 1 || spr < 1 || H < 1 || I < 1) return METRO_ERR_INVALID_ARG;
-    if (dtype != METRO_DTYPE_BF16 && dtype != METRO_DTYPE_F32) return METRO_ERR_UNSUPPORTED;
-    if (spr > kMaxSpr || (int64_t)T * k >= (1 << 24)) return METRO_ERR_UNSUPPORTED;
-    if ((((uintptr_t)x | (uintptr_t)w13 | (uintptr_t)w2 | (uintptr_t)y_perm) & 15) != 0 || ((uintptr_t)ws & 255) != 0)
-        return METRO_ERR_INVALID_ARG;
-    if (ws_bytes < moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, dtype)) return METRO_ERR_WORKSPACE;
+    const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
+    if (rc != METRO_OK) return rc;
+    const int cap = T * k;
+    if (cap == 0 || !mfma_shape(H, I, dtype)) return METRO_OK;    // the general kernels need no plan
+    const Workspace w = carve(ws, cap, spr);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kWave), 0, (hipStream_t)stream, group_offsets, spr, cap,
+                       w.tile_cap, w.hdr, w.tiles);
+    return launched();
+}
+
+extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T,
+                                       int k, int spr, int H, int I, int dtype, const void* w13, void* ws,
+                                       size_t ws_bytes, void* stream) {
+    using namespace metro;
+    const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
+    if (rc != METRO_OK) return rc;
+    if (!x || !perm_pair || !w13 || (((uintptr_t)x | (uintptr_t)w13) & 15) != 0) return METRO_ERR_INVALID_ARG;
     const int cap = T * k;
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
-    char* base = (char*)ws;
-    PlanHeader* hdr = (PlanHeader*)base;
-    Tile* tiles = (Tile*)(base + kPlanBytes);
-    const int mt = max_tiles(cap, spr);
-    char* act = base + kPlanBytes + align256(sizeof(Tile) * (size_t)mt);
-
+    const Workspace w = carve(ws, cap, spr);
     if (!mfma_shape(H, I, dtype)) {
+        const int per = kThreads / kWave;
+        const dim3 grid(cap, (I + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
-            return launch_general<float>(x, perm_pair, group_offsets, T, k, spr, H, I, w13, w2, y_perm,
-                                         (float*)act, st);
-        return launch_general<__bf16>(x, perm_pair, group_offsets, T, k, spr, H, I, w13, w2, y_perm, (float*)act,
-                                      st);
+            hipLaunchKernelGGL(general_gate_up_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x,
+                               perm_pair, group_offsets, T, k, spr, H, I, (const float*)w13, (float*)w.act);
+        else
+            hipLaunchKernelGGL(general_gate_up_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const __bf16*)x,
+                               perm_pair, group_offsets, T, k, spr, H, I, (const __bf16*)w13, (float*)w.act);
+        return launched();
     }
-
-    static bool lds_ok = false;                    // opt in to > 64 KB of dynamic LDS, once
-    if (!lds_ok) {
-        if (hipFuncSetAttribute((const void*)ffn_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes) != hipSuccess ||
-            hipFuncSetAttribute((const void*)ffn_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes) != hipSuccess)
-            return METRO_ERR_HIP;
-        lds_ok = true;
-    }
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kWave), 0, st, group_offsets, spr, cap, mt, hdr, tiles);
+    if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
     FfnArgs a;
-    a.perm_pair = perm_pair;
-    a.hdr = hdr;
-    a.tiles = tiles;
-    a.T = T; a.k = k; a.H = H; a.I = I;
     a.src = (const __bf16*)x;
+    a.perm_pair = perm_pair;
     a.w = (const __bf16*)w13;
-    a.dst = (__bf16*)act;
-    a.n_ntiles = I / 64;
-    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(mt * a.n_ntiles), dim3(kThreads), kLdsBytes, st, a);
-    a.src = (const __bf16*)act;
+    a.dst = (__bf16*)w.act;
+    a.hdr = w.hdr;
+    a.tiles = w.tiles;
+    a.T = T; a.k = k; a.H = H; a.I = I;
+    a.nt_wide = I / 128;
+    a.nt_stream = I / 64;
+    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(w.tile_cap * a.nt_stream), dim3(kThreads), kLdsBytes, st, a);
+    return launched();
+}
+
+extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
+                                    const void* w2, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
+    using namespace metro;
+    const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
+    if (rc != METRO_OK) return rc;
+    if (!w2 || !y_perm || (((uintptr_t)w2 | (uintptr_t)y_perm) & 15) != 0) return METRO_ERR_INVALID_ARG;
+    const int cap = T * k;
+    if (cap == 0) return METRO_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const Workspace w = carve(ws, cap, spr);
+    if (!mfma_shape(H, I, dtype)) {
+        const int per = kThreads / kWave;
+        const dim3 grid(cap, (H + per - 1) / per);
+        if (dtype == METRO_DTYPE_F32)
+            hipLaunchKernelGGL(general_down_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)w.act,
+                               group_offsets, spr, H, I, (const float*)w2, (float*)y_perm);
+        else
+            hipLaunchKernelGGL(general_down_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const float*)w.act,
+                               group_offsets, spr, H, I, (const __bf16*)w2, (__bf16*)y_perm);
+        return launched();
+    }
+    if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
+    FfnArgs a;
+    a.src = (const __bf16*)w.act;
+    a.perm_pair = nullptr;
     a.w = (const __bf16*)w2;
     a.dst = (__bf16*)y_perm;
-    a.n_ntiles = H / 128;
-    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(mt * a.n_ntiles), dim3(kThreads), kLdsBytes, st, a);
-    return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
+    a.hdr = w.hdr;
+    a.tiles = w.tiles;
+    a.T = T; a.k = k; a.H = H; a.I = I;
+    a.nt_wide = (H + 255) / 256;
+    a.nt_stream = H / 128;
+    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(w.tile_cap * a.nt_stream), dim3(kThreads), kLdsBytes, st, a);
+    return launched();
+}
+
+extern "C" int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
+                               int spr, int H, int I, int dtype, const void* w13, const void* w2, void* y_perm,
+                               void* ws, size_t ws_bytes, void* stream) {
+    // all arguments are checked before the first launch
+    if (!x || !perm_pair || !w13 || !w2 || !y_perm) return METRO_ERR_INVALID_ARG;
+    if ((((uintptr_t)x | (uintptr_t)w13 | (uintptr_t)w2 | (uintptr_t)y_perm) & 15) != 0) return METRO_ERR_INVALID_ARG;
+    int rc = moe_grouped_ffn_plan(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes, stream);
+    if (rc == METRO_OK)
+        rc = moe_grouped_ffn_gate_up(x, perm_pair, group_offsets, T, k, spr, H, I, dtype, w13, ws, ws_bytes, stream);
+    if (rc == METRO_OK) rc = moe_grouped_ffn_down(group_offsets, T, k, spr, H, I, dtype, w2, y_perm, ws, ws_bytes, stream);
+    return rc;
 }
