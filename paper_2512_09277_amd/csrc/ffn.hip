@@ -204,7 +204,7 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     }
     const int wr_off = frow * kLdsRow + fchunk * 16;
     const int rd_off = r16 * kLdsRow + q * 16;
-    constexpr int kLdsBuf = MT * 16 * kLdsRow;
+    constexpr int kLdsBuf = NP * kRowsPerPass * kLdsRow;   // staged rows past 16*MT are never read
 
     floatx4 acc[NB][MT];
 #pragma unroll
@@ -225,14 +225,12 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     auto load_x = [&](int set, int step) {
 #pragma unroll
         for (int pz = 0; pz < NP; ++pz)
-            if (NP * kRowsPerPass <= MT * 16 || pz * kRowsPerPass + frow < MT * 16)
-                xr[set][pz] = *reinterpret_cast<const u32x4*>(px[pz] + (size_t)step * (BK * 2));
+            xr[set][pz] = *reinterpret_cast<const u32x4*>(px[pz] + (size_t)step * (BK * 2));
     };
     auto park_x = [&](int set, int buf) {
 #pragma unroll
         for (int pz = 0; pz < NP; ++pz)
-            if (NP * kRowsPerPass <= MT * 16 || pz * kRowsPerPass + frow < MT * 16)
-                *reinterpret_cast<u32x4*>(lds + buf * kLdsBuf + wr_off + pz * kRowsPerPass * kLdsRow) = xr[set][pz];
+            *reinterpret_cast<u32x4*>(lds + buf * kLdsBuf + wr_off + pz * kRowsPerPass * kLdsRow) = xr[set][pz];
     };
 
     // Every load below is unconditional (past the last step the index is clamped, which re-reads
