@@ -61,7 +61,12 @@ class HotPath:
             w13, w2 = self.shares[g]
             nbytes = w13.numel() * w13.element_size() + w2.numel() * w2.element_size()
             n = max(1, -(-1536 * 2**20 // nbytes))
-            self.copies[g] = [(w13, w2)] + [(w13.clone(), w2.clone()) for _ in range(n - 1)]
+            def same_layout(t):
+                c = torch.empty_strided(t.size(), t.stride(), dtype=t.dtype, device=t.device)
+                c.copy_(t)
+                return c
+
+            self.copies[g] = [(w13, w2)] + [(same_layout(w13), same_layout(w2)) for _ in range(n - 1)]
         c = self.copies[g]
         self.calls += 1
         return c[self.calls % len(c)]
@@ -178,6 +183,9 @@ def main() -> int:
     ap.add_argument("--only-metro", action="store_true", help="skip the token-balanced comparison and the sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle FFN work")
+    ap.add_argument("--dense-weights", action="store_true",
+                    help="weight rows back to back (default: rows of a multiple of 1024 bytes are padded by 128 "
+                         "elements, the layout the library recommends)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -208,7 +216,9 @@ def main() -> int:
     tw = torch.from_numpy(W.gating_weights(w.T, w.k, w.seed(0, 4))).cuda()
     lw13, lw2 = W.device_expert_weights(w, "cuda")
     ranks = range(w.G) if args.rank < 0 else [args.rank]
-    shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr), W.device_rank_share(lw2, s2e, g, w.spr)) for g in ranks}
+    pad = not args.dense_weights
+    shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr, pad=pad), W.device_rank_share(lw2, s2e, g, w.spr, pad=pad))
+              for g in ranks}
     del lw13, lw2
     torch.cuda.synchronize()
 
@@ -252,7 +262,8 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(me["ms_per_step"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "E": w.N, "top_k": w.k, "G_logical_ranks": w.G, "slots_per_rank": w.spr,
-                   "T": w.T, "zipf_s": w.s, "H": w.H, "I": w.I, "measured_rank": me["rank"], "routing": "metro"},
+                   "T": w.T, "zipf_s": w.s, "H": w.H, "I": w.I, "measured_rank": me["rank"], "routing": "metro",
+                   "weight_row_pitch": {"w13": shares[me["rank"]][0].stride(1), "w2": shares[me["rank"]][1].stride(1)}},
         "route_us_per_batch": me["stage_us"]["route"],
         "ffn_us": {"metro": round(me["ffn_us"], 1)},
         "max_activated_per_rank": {"metro": me["lam"]},
@@ -278,7 +289,7 @@ def main() -> int:
 
         oracle.build()
         g = me["rank"]
-        host = lambda t: t.cpu().view(torch.int16).numpy().view(np.uint16)
+        host = lambda t: t.contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
         perm = dict(me["perm"])
         perm["n_pairs"] = int(perm["n_pairs"][0])
         line["cpu_baseline"] = cpu_baseline(oracle, W, w, ids, s2e, host(x), host(shares[g][0]), host(shares[g][1]),

@@ -101,8 +101,15 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
  *     y_perm[r] = (silu(gate) * up) . w2[l]^T
  *
  *   x      [T,H]       dtype   activations of the whole batch
- *   w13    [spr,2I,H]  dtype   per local slot: rows 0..I-1 gate, I..2I-1 up (H contiguous)
- *   w2     [spr,H,I]   dtype   per local slot: down projection (I contiguous)
+ *   w13    [spr,2I,H]  dtype   per local slot: rows 0..I-1 gate, I..2I-1 up (H contiguous);
+ *                              consecutive rows are ldw13 >= H elements apart, slots 2I*ldw13
+ *   w2     [spr,H,I]   dtype   per local slot: down projection (I contiguous), rows ldw2 >= I
+ *                              elements apart, slots H*ldw2
+ *   ldw13, ldw2                row pitches in elements, multiples of 8.  The weights are the
+ *                              library's to lay out: a pitch that is a multiple of 4096 bytes makes
+ *                              the 16 rows of one load instruction fall on the same few HBM
+ *                              channels (measured: 5.3 instead of 6.2 TB/s at a 4096-byte pitch),
+ *                              so pad such rows, e.g. by 128 elements.
  *   y_perm [T*k,H]     dtype   out: rows 0..n_pairs-1 are written
  *   ws                         workspace of moe_grouped_ffn_workspace_bytes(); 256-byte aligned
  *   dtype  METRO_DTYPE_BF16: bf16 storage, fp32 accumulation on the matrix cores, the
@@ -112,8 +119,8 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
  */
 size_t moe_grouped_ffn_workspace_bytes(int T, int k, int spr, int H, int I, int dtype);
 int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
-                    int spr, int H, int I, int dtype, const void* w13, const void* w2, void* y_perm,
-                    void* ws, size_t ws_bytes, void* stream);
+                    int spr, int H, int I, int dtype, const void* w13, int ldw13, const void* w2, int ldw2,
+                    void* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The three stages of moe_grouped_ffn as separate calls, in the order plan -> gate_up -> down, on
@@ -126,10 +133,10 @@ int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* grou
 int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype, void* ws,
                          size_t ws_bytes, void* stream);
 int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
-                            int spr, int H, int I, int dtype, const void* w13, void* ws, size_t ws_bytes,
-                            void* stream);
+                            int spr, int H, int I, int dtype, const void* w13, int ldw13, void* ws,
+                            size_t ws_bytes, void* stream);
 int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
-                         const void* w2, void* y_perm, void* ws, size_t ws_bytes, void* stream);
+                         const void* w2, int ldw2, void* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * moe_unpermute -- the rank's share of the combine step (Sec. 2.2): for every token,

@@ -51,13 +51,13 @@ def load() -> ctypes.CDLL:
         lib.moe_grouped_ffn_workspace_bytes.restype = sz
         lib.moe_grouped_ffn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
         lib.moe_grouped_ffn.restype = ci
-        lib.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        lib.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, ci, vp, vp, sz, vp]
         lib.moe_grouped_ffn_plan.restype = ci
         lib.moe_grouped_ffn_plan.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
         lib.moe_grouped_ffn_gate_up.restype = ci
-        lib.moe_grouped_ffn_gate_up.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, sz, vp]
+        lib.moe_grouped_ffn_gate_up.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, sz, vp]
         lib.moe_grouped_ffn_down.restype = ci
-        lib.moe_grouped_ffn_down.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+        lib.moe_grouped_ffn_down.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, sz, vp]
         lib.moe_unpermute.restype = ci
         lib.moe_unpermute.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
         _lib = lib
@@ -77,6 +77,18 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> int:
     if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"{name}: expected a contiguous {dtype} device tensor, got {t.dtype} on {t.device}")
     return t.data_ptr()
+
+
+def _weights(t: torch.Tensor, dtype: torch.dtype, name: str):
+    """Weights [slots, rows, K]: K contiguous, rows `ld` elements apart, slots rows*ld apart (a dense
+    tensor, or a [:, :, :K] view of a buffer with padded rows).  Returns (pointer, ld)."""
+    if not (t.is_cuda and t.dtype == dtype and t.dim() == 3):
+        raise TypeError(f"{name}: expected a 3-d {dtype} device tensor")
+    slots, rows, K = t.shape
+    ld = t.stride(1) if rows > 1 else max(K, t.stride(1))
+    if t.stride(2) != 1 or ld < K or (slots > 1 and t.stride(0) != rows * ld):
+        raise TypeError(f"{name}: rows must be K-contiguous with a uniform pitch (strides {t.stride()})")
+    return t.data_ptr(), ld
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -175,11 +187,12 @@ def moe_grouped_ffn(x: torch.Tensor, perm_pair: torch.Tensor, group_offsets: tor
     need = int(load().moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, code))
     if ws is None:
         ws = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    p13, ld13 = _weights(w13, x.dtype, "w13")
+    p2, ld2 = _weights(w2, x.dtype, "w2")
     _check(load().moe_grouped_ffn(_dev(x, x.dtype, "x"), _dev(perm_pair, torch.int32, "perm_pair"),
                                   _dev(group_offsets, torch.int32, "group_offsets"), T, k, spr, H, I, code,
-                                  _dev(w13, x.dtype, "w13"), _dev(w2, x.dtype, "w2"),
-                                  _dev(y_perm, x.dtype, "y_perm"), _dev(ws, torch.uint8, "ws"), ws.numel(),
-                                  _stream()))
+                                  p13, ld13, p2, ld2, _dev(y_perm, x.dtype, "y_perm"),
+                                  _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
     return y_perm
 
 
@@ -196,12 +209,14 @@ def moe_grouped_ffn_stages(x, perm_pair, group_offsets, k: int, w13, w2, y_perm,
     mark = between if between is not None else (lambda i: None)
     mark(0)
     _check(lib.moe_grouped_ffn_plan(go, T, k, spr, H, I, code, wsp, wsn, _stream()))
+    p13, ld13 = _weights(w13, x.dtype, "w13")
+    p2, ld2 = _weights(w2, x.dtype, "w2")
     mark(1)
     _check(lib.moe_grouped_ffn_gate_up(_dev(x, x.dtype, "x"), _dev(perm_pair, torch.int32, "perm_pair"), go, T, k,
-                                       spr, H, I, code, _dev(w13, x.dtype, "w13"), wsp, wsn, _stream()))
+                                       spr, H, I, code, p13, ld13, wsp, wsn, _stream()))
     mark(2)
-    _check(lib.moe_grouped_ffn_down(go, T, k, spr, H, I, code, _dev(w2, x.dtype, "w2"),
-                                    _dev(y_perm, x.dtype, "y_perm"), wsp, wsn, _stream()))
+    _check(lib.moe_grouped_ffn_down(go, T, k, spr, H, I, code, p2, ld2, _dev(y_perm, x.dtype, "y_perm"), wsp, wsn,
+                                    _stream()))
     mark(3)
     return y_perm
 

@@ -93,7 +93,8 @@ struct FfnArgs {
     const PlanHeader* hdr;
     const Tile* tiles;
     int T, k, H, I;
-    int nt_wide, nt_stream;   // column tiles per wide / stream tile
+    int ldw;                  // elements between consecutive weight rows (>= K)
+    int nt_wide, nt_stream;   // workgroups per wide / stream tile
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -181,14 +182,14 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     const int col0 = nt * 4 * cols_per_wave + wv * cols_per_wave;     // first output column of the wave
 
     // weight row of block b: gate/up pairs block b (gate) with block b + NB/2 (up)
-    const __bf16* wbase = a.w + (size_t)t.slot * (kGateUp ? (size_t)2 * I * H : (size_t)H * I);
+    const __bf16* wbase = a.w + (size_t)t.slot * (kGateUp ? (size_t)2 * I : (size_t)H) * a.ldw;
     const char* pw[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         int col = kGateUp ? col0 + (b % (NB / 2)) * 16 : col0 + b * 16;
         col = col < n_out ? col : n_out - 16;   // a block past the last column repeats the last block
         const int row = (kGateUp && b >= NB / 2) ? I + col + r16 : col + r16;
-        pw[b] = reinterpret_cast<const char*>(wbase + (size_t)row * K) + q * 16;
+        pw[b] = reinterpret_cast<const char*>(wbase + (size_t)row * a.ldw) + q * 16;
     }
 
     // activation staging: thread (frow, fchunk) copies 16 bytes of rows frow, frow + kRowsPerPass, ...
@@ -237,21 +238,22 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     // the last step): the compiler can then count outstanding loads exactly and waits only for
     // the ones a step consumes, instead of draining the queue at every branch join.
     const int last = n_steps - 1;
+    // (the weight addresses need only the tile, the activation addresses also need perm_pair: the
+    // weight loads go out first so that they overlap that extra round trip)
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) load_w(d, min(d, last));
     load_x(0, 0);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-        if (d >= 1) load_x(d % DEPTH, min(d, last));
-        load_w(d, min(d, last));
-    }
+    for (int d = 1; d < DEPTH; ++d) load_x(d % DEPTH, min(d, last));
     park_x(0, 0);
     __syncthreads();
 
-    // One K step with compile-time buffer indices u (step s = u mod kPeriod).
-    auto do_step = [&](auto U, int s) {
+    // One K step with compile-time buffer indices u (= step s mod kPeriod).
+    auto do_step = [&](auto U, const int s) {
         constexpr int u = decltype(U)::value;
         // Loads retire in issue order: the activations go first so that waiting for them (to park
         // them one step later) never waits for the younger weight loads.
-        const int ps = min(s + DEPTH, last);
+        const int ps = min(s + DEPTH, last);                          // past the end: re-read the last step
         load_x(u % DEPTH, ps);
         load_w((u + DEPTH) % NW, ps);
         const char* cur = lds + (u % 2) * kLdsBuf + rd_off;
@@ -268,7 +270,7 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
                 }
             }
         }
-        // activations of step s+1 were loaded DEPTH-1 steps ago (set (s+1) % DEPTH)
+        // activations of the next step were loaded DEPTH-1 steps ago (set (u+1) % DEPTH)
         park_x((u + 1) % DEPTH, (u + 1) % 2);
         __syncthreads();
     };
@@ -276,7 +278,6 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     int s0 = 0;
     for (; s0 + kPeriod <= n_steps; s0 += kPeriod) run_steps(std::make_integer_sequence<int, kPeriod>{}, do_step, s0);
     run_steps_tail(std::make_integer_sequence<int, kPeriod - 1>{}, do_step, s0, n_steps);
-
     store_tile<kGateUp, NB, MT>(a, t, acc, col0, n_out, mt_count, r16, q);
 }
 
@@ -290,7 +291,9 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     const int n_wide = a.hdr->n_wide, n_stream = a.hdr->n_stream;
     // Work items = (tile, column tile), wide tiles first: a wide workgroup lives several times longer
     // than a stream one, so it has to start early for the stream items to fill in around it.
-    int id = blockIdx.x;                                     // everything below is uniform per workgroup
+    // (Measured alternatives that lost: spreading the wide items through the launch order, and
+    // alternating wide and stream items.)  Everything here is uniform per workgroup.
+    int id = blockIdx.x;
     const int wide_items = n_wide * a.nt_wide;
     if (id < wide_items) {
         const int ti = id / a.nt_wide;
@@ -301,8 +304,9 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     const int ti = id / a.nt_stream;
     if (ti >= n_stream) return;
     const Tile t = a.tiles[n_wide + ti];
-    if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, id - ti * a.nt_stream, lds);
-    else ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, id - ti * a.nt_stream, lds);
+    const int nt = id - ti * a.nt_stream;
+    if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, nt, lds);
+    else ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, nt, lds);
 }
 
 // ------------------------------------------------------------------------------------------ general path
@@ -342,15 +346,16 @@ __global__ __launch_bounds__(kThreads) void general_gate_up_kernel(const T* __re
                                                                    const int32_t* __restrict__ perm_pair,
                                                                    const int32_t* __restrict__ group_offsets, int Tn,
                                                                    int k, int spr, int H, int I,
-                                                                   const T* __restrict__ w13, float* __restrict__ act) {
+                                                                   const T* __restrict__ w13, int ldw,
+                                                                   float* __restrict__ act) {
     const int r = blockIdx.x;                     // < T*k by the launch grid
     if (r >= group_offsets[spr]) return;
     const int i = blockIdx.y * (kThreads / kWave) + wave_id();
     if (i >= I) return;
     const int l = slot_of_row(group_offsets, spr, r);
     const T* xr = x + (size_t)min(max(perm_pair[r] / k, 0), Tn - 1) * H;
-    const T* wg = w13 + ((size_t)l * 2 * I + i) * H;
-    const T* wu = wg + (size_t)I * H;
+    const T* wg = w13 + ((size_t)l * 2 * I + i) * ldw;
+    const T* wu = wg + (size_t)I * ldw;
     float g = 0.f, u = 0.f;
     for (int h = lane_id(); h < H; h += kWave) {
         const float xv = to_f32<T>(xr[h]);
@@ -365,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void general_gate_up_kernel(const T* __re
 template <typename T>
 __global__ __launch_bounds__(kThreads) void general_down_kernel(const float* __restrict__ act,
                                                                 const int32_t* __restrict__ group_offsets, int spr,
-                                                                int H, int I, const T* __restrict__ w2,
+                                                                int H, int I, const T* __restrict__ w2, int ldw,
                                                                 T* __restrict__ y) {
     const int r = blockIdx.x;
     if (r >= group_offsets[spr]) return;
@@ -373,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void general_down_kernel(const float* __r
     if (c >= H) return;
     const int l = slot_of_row(group_offsets, spr, r);
     const float* ar = act + (size_t)r * I;
-    const T* wd = w2 + ((size_t)l * H + c) * I;
+    const T* wd = w2 + ((size_t)l * H + c) * ldw;
     float acc = 0.f;
     for (int i = lane_id(); i < I; i += kWave) acc = fmaf(ar[i], to_f32<T>(wd[i]), acc);
     acc = wave_sum(acc);
@@ -456,12 +461,13 @@ extern "C" int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, 
 }
 
 extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T,
-                                       int k, int spr, int H, int I, int dtype, const void* w13, void* ws,
-                                       size_t ws_bytes, void* stream) {
+                                       int k, int spr, int H, int I, int dtype, const void* w13, int ldw13,
+                                       void* ws, size_t ws_bytes, void* stream) {
     using namespace metro;
     const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
     if (rc != METRO_OK) return rc;
     if (!x || !perm_pair || !w13 || (((uintptr_t)x | (uintptr_t)w13) & 15) != 0) return METRO_ERR_INVALID_ARG;
+    if (ldw13 < H || ldw13 % 8 != 0) return METRO_ERR_INVALID_ARG;
     const int cap = T * k;
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
@@ -471,10 +477,10 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
         const dim3 grid(cap, (I + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
             hipLaunchKernelGGL(general_gate_up_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x,
-                               perm_pair, group_offsets, T, k, spr, H, I, (const float*)w13, (float*)w.act);
+                               perm_pair, group_offsets, T, k, spr, H, I, (const float*)w13, ldw13, (float*)w.act);
         else
             hipLaunchKernelGGL(general_gate_up_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const __bf16*)x,
-                               perm_pair, group_offsets, T, k, spr, H, I, (const __bf16*)w13, (float*)w.act);
+                               perm_pair, group_offsets, T, k, spr, H, I, (const __bf16*)w13, ldw13, (float*)w.act);
         return launched();
     }
     if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
@@ -482,6 +488,7 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     a.src = (const __bf16*)x;
     a.perm_pair = perm_pair;
     a.w = (const __bf16*)w13;
+    a.ldw = ldw13;
     a.dst = (__bf16*)w.act;
     a.hdr = w.hdr;
     a.tiles = w.tiles;
@@ -493,11 +500,13 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
 }
 
 extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
-                                    const void* w2, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
+                                    const void* w2, int ldw2, void* y_perm, void* ws, size_t ws_bytes,
+                                    void* stream) {
     using namespace metro;
     const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
     if (rc != METRO_OK) return rc;
     if (!w2 || !y_perm || (((uintptr_t)w2 | (uintptr_t)y_perm) & 15) != 0) return METRO_ERR_INVALID_ARG;
+    if (ldw2 < I || ldw2 % 8 != 0) return METRO_ERR_INVALID_ARG;
     const int cap = T * k;
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
@@ -507,10 +516,10 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
         const dim3 grid(cap, (H + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
             hipLaunchKernelGGL(general_down_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)w.act,
-                               group_offsets, spr, H, I, (const float*)w2, (float*)y_perm);
+                               group_offsets, spr, H, I, (const float*)w2, ldw2, (float*)y_perm);
         else
             hipLaunchKernelGGL(general_down_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const float*)w.act,
-                               group_offsets, spr, H, I, (const __bf16*)w2, (__bf16*)y_perm);
+                               group_offsets, spr, H, I, (const __bf16*)w2, ldw2, (__bf16*)y_perm);
         return launched();
     }
     if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
@@ -518,6 +527,7 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     a.src = (const __bf16*)w.act;
     a.perm_pair = nullptr;
     a.w = (const __bf16*)w2;
+    a.ldw = ldw2;
     a.dst = (__bf16*)y_perm;
     a.hdr = w.hdr;
     a.tiles = w.tiles;
@@ -529,14 +539,17 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
 }
 
 extern "C" int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
-                               int spr, int H, int I, int dtype, const void* w13, const void* w2, void* y_perm,
-                               void* ws, size_t ws_bytes, void* stream) {
+                               int spr, int H, int I, int dtype, const void* w13, int ldw13, const void* w2,
+                               int ldw2, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
     // all arguments are checked before the first launch
     if (!x || !perm_pair || !w13 || !w2 || !y_perm) return METRO_ERR_INVALID_ARG;
     if ((((uintptr_t)x | (uintptr_t)w13 | (uintptr_t)w2 | (uintptr_t)y_perm) & 15) != 0) return METRO_ERR_INVALID_ARG;
+    if (ldw13 < H || ldw2 < I || ldw13 % 8 != 0 || ldw2 % 8 != 0) return METRO_ERR_INVALID_ARG;
     int rc = moe_grouped_ffn_plan(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes, stream);
     if (rc == METRO_OK)
-        rc = moe_grouped_ffn_gate_up(x, perm_pair, group_offsets, T, k, spr, H, I, dtype, w13, ws, ws_bytes, stream);
-    if (rc == METRO_OK) rc = moe_grouped_ffn_down(group_offsets, T, k, spr, H, I, dtype, w2, y_perm, ws, ws_bytes, stream);
+        rc = moe_grouped_ffn_gate_up(x, perm_pair, group_offsets, T, k, spr, H, I, dtype, w13, ldw13, ws, ws_bytes,
+                                     stream);
+    if (rc == METRO_OK)
+        rc = moe_grouped_ffn_down(group_offsets, T, k, spr, H, I, dtype, w2, ldw2, y_perm, ws, ws_bytes, stream);
     return rc;
 }

@@ -244,11 +244,23 @@ def device_activations(w: Workload, device, layer: int = 0, T: Optional[int] = N
     return torch.randn((w.T if T is None else T, w.H), generator=gen, device=device).to(dt)
 
 
-def device_rank_share(wt, slot_to_expert: np.ndarray, g: int, spr: int):
-    """Device copy of rank g's slots, [spr, ...]; empty slots hold zeros."""
+def padded_pitch(K: int, elt_bytes: int = 2) -> int:
+    """Row pitch in elements for weight rows of K elements: rows whose byte length is a multiple of
+    1024 get 128 more elements, so that the rows one load instruction touches spread over the HBM
+    channels instead of piling onto a few of them."""
+    return K + 128 if (K * elt_bytes) % 1024 == 0 else K
+
+
+def device_rank_share(wt, slot_to_expert: np.ndarray, g: int, spr: int, pad: bool = False):
+    """Device copy of rank g's slots, [spr, rows, K]; empty slots hold zeros.  pad=True returns a view
+    of a buffer whose rows are padded_pitch(K) elements apart (same values, different layout)."""
     import torch
 
     ex = torch.as_tensor(slot_to_expert[g * spr:(g + 1) * spr].astype(np.int64), device=wt.device)
-    out = wt.index_select(0, ex.clamp(min=0)).contiguous()
+    K = wt.shape[2]
+    ld = padded_pitch(K, wt.element_size()) if pad else K
+    buf = torch.zeros((spr, wt.shape[1], ld), dtype=wt.dtype, device=wt.device)
+    out = buf[:, :, :K]
+    out.copy_(wt.index_select(0, ex.clamp(min=0)))
     out[ex < 0] = 0
     return out

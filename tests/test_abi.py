@@ -63,10 +63,12 @@ def test_host_side_argument_checks(lib):
     assert lib.moe_unpermute(one, one, one, 4, 2, 16, 7, one, None) == -2                       # dtype
     need = lib.moe_grouped_ffn_workspace_bytes(4, 2, 3, 256, 128, 1)
     assert need >= 4 * 2 * 128 * 2
-    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 1, one, one, one, one, need - 1, None) == -3
-    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 1, ctypes.c_void_p(8), one, one, one, need,
-                               None) == -1                                                     # misaligned w13
-    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 5, one, one, one, one, need, None) == -2
+    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 1, one, 256, one, 128, one, one, need - 1, None) == -3
+    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 1, ctypes.c_void_p(8), 256, one, 128, one, one,
+                               need, None) == -1                                               # misaligned w13
+    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 1, one, 255, one, 128, one, one, need,
+                               None) == -1                                                     # pitch < H
+    assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 5, one, 256, one, 128, one, one, need, None) == -2
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):

@@ -255,6 +255,38 @@ def test_ragged_groups_span_tiles(api, oracle, dtype, H, I, tol):
     run_rank(api, oracle, x, w13, w2, tw, ps, 2, spr, k, tol)
 
 
+@pytest.mark.parametrize("dtype,H,I,tol", [("bf16", 512, 256, BF16_TOL), ("f32", 200, 72, F32_TOL)])
+def test_padded_weight_rows(api, oracle, dtype, H, I, tol):
+    """Weights stored with a row pitch larger than the row (the layout the benchmark uses): same result."""
+    import torch
+
+    sizes = [17, 0, 140, 5]
+    spr, k, T = len(sizes), 2, 120
+    rng = np.random.default_rng(3)
+    pairs = rng.permutation(T * k)[:sum(sizes)]
+    ps = np.full(T * k, -1, np.int32)
+    at = 0
+    for l, m in enumerate(sizes):
+        ps[pairs[at:at + m]] = l
+        at += m
+    ps = ps.reshape(T, k)
+    x = W.activations(T, H, 5, dtype)
+    w13, w2 = W.expert_weights(spr, H, I, 6, dtype)
+
+    def padded(a, extra):
+        t = dev_fp(a)
+        buf = torch.full((t.shape[0], t.shape[1], t.shape[2] + extra), 7.0, dtype=t.dtype, device="cuda")
+        view = buf[:, :, :t.shape[2]]
+        view.copy_(t)
+        return view
+
+    pm = api.moe_permute(dev_i32(ps), 0, spr)
+    y = api.moe_grouped_ffn(dev_fp(x), pm["perm_pair"], pm["group_offsets"], k, padded(w13, 128), padded(w2, 64))
+    ref_pm = oracle.permute(ps, 0, spr)
+    ref = oracle.ffn(x, ref_pm["perm_pair"], ref_pm["group_offsets"], k, w13, w2)
+    assert rel_err(host_f64(y)[:ref_pm["n_pairs"]], ref) <= tol
+
+
 def test_empty_rank_ffn(api):
     """No pair on the rank: nothing is written, nothing faults."""
     import torch
@@ -287,8 +319,8 @@ def test_full_size_sampled_rows(api, oracle, w):
     g = int(np.argmax(np.bincount(ps.reshape(-1) // w.spr, minlength=w.G)))
     print(f"full size {w.name}: rank {g}", flush=True)
     lw13, lw2 = W.device_expert_weights(w, "cuda")
-    w13 = W.device_rank_share(lw13, s2e, g, w.spr)
-    w2 = W.device_rank_share(lw2, s2e, g, w.spr)
+    w13 = W.device_rank_share(lw13, s2e, g, w.spr, pad=True)       # the layout bench.py times
+    w2 = W.device_rank_share(lw2, s2e, g, w.spr, pad=True)
     del lw13, lw2
     x = W.device_activations(w, "cuda")
     tw = W.gating_weights(w.T, w.k, w.seed(0, 4))
@@ -306,7 +338,7 @@ def test_full_size_sampled_rows(api, oracle, w):
     rng = np.random.default_rng(1)
     rows = sorted({int(go[widest]), int(go[widest + 1] - 1), int(go[small]), int(go[small + 1] - 1), 0, n - 1,
                    *rng.integers(0, n, size=10).tolist()})
-    host = lambda t: t.cpu().view(torch.int16).numpy().view(np.uint16)
+    host = lambda t: t.contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
     ref_y = oracle.ffn(host(x), ref_pm["perm_pair"], go, w.k, host(w13), host(w2), rows=rows)
     got_y = host_f64(y[torch.as_tensor(rows, device="cuda")])
     assert rel_err(got_y, ref_y) <= BF16_TOL, rel_err(got_y, ref_y)
