@@ -52,12 +52,29 @@ struct OrderedCounter {
         for (int i = threadIdx.x; i < n_waves * n_keys; i += blockDim.x) hist[i] = 0;
     }
 
-    // key_of(item) -> key in [0, n_keys) or -1 to leave the item out.  Call between barriers.
+    static constexpr int kCached = 8;   // chunks per wave whose keys stay in registers between the passes
+
+    // Keys of this wave's first kCached chunks, fetched with independent loads (one round trip for
+    // all of them).  key_of(item) -> key in [0, n_keys) or -1 to leave the item out.
     template <typename KeyFn>
-    __device__ __forceinline__ void histogram(KeyFn key_of) {
+    __device__ __forceinline__ void load_keys(KeyFn key_of, int (&keys)[kCached]) const {
+        const int first = wave_id() * chunks_per_wave;
+#pragma unroll
+        for (int c = 0; c < kCached; ++c) {
+            const int item = (first + c) * kWave + lane_id();
+            keys[c] = (c < chunks_per_wave && item < n) ? key_of(item) : -1;
+        }
+    }
+
+    // Per-wave histogram.  Call between barriers.
+    template <typename KeyFn>
+    __device__ __forceinline__ void histogram(KeyFn key_of, const int (&keys)[kCached]) {
         int* mine = hist + wave_id() * n_keys;
         const int first = wave_id() * chunks_per_wave;
-        for (int c = first; c < first + chunks_per_wave; ++c) {
+#pragma unroll
+        for (int c = 0; c < kCached; ++c)
+            if (keys[c] >= 0) atomicAdd(&mine[keys[c]], 1);
+        for (int c = first + kCached; c < first + chunks_per_wave; ++c) {
             const int item = c * kWave + lane_id();
             if (item < n) {
                 const int key = key_of(item);
@@ -83,13 +100,10 @@ struct OrderedCounter {
     // emit(item, key, occ) for every item: occ = number of earlier items with the same key
     // (key = -1: occ undefined).  Call between barriers.
     template <typename KeyFn, typename EmitFn>
-    __device__ __forceinline__ void number(KeyFn key_of, EmitFn emit) {
+    __device__ __forceinline__ void number(KeyFn key_of, const int (&keys)[kCached], EmitFn emit) {
         int* mine = hist + wave_id() * n_keys;
         const int first = wave_id() * chunks_per_wave;
-        for (int c = first; c < first + chunks_per_wave; ++c) {   // uniform per wave
-            const int item = c * kWave + lane_id();
-            const bool in_range = item < n;
-            const int key = in_range ? key_of(item) : -1;
+        auto one_chunk = [&](int c, int key, bool in_range) {
             const bool valid = key >= 0;
             int total;
             const int rank = wave_rank_by_key(key, valid, total);
@@ -97,7 +111,16 @@ struct OrderedCounter {
             if (valid) occ = mine[key] + rank;
             // the wave executes in lockstep: every read of mine[] above precedes the update below
             if (valid && rank == total - 1) mine[key] = occ + 1;
-            if (in_range) emit(item, key, occ);
+            if (in_range) emit(c * kWave + lane_id(), key, occ);
+        };
+#pragma unroll
+        for (int c = 0; c < kCached; ++c)
+            if (c < chunks_per_wave)                                   // uniform per wave
+                one_chunk(first + c, keys[c], (first + c) * kWave + lane_id() < n);
+        for (int c = first + kCached; c < first + chunks_per_wave; ++c) {
+            const int item = c * kWave + lane_id();
+            const bool in_range = item < n;
+            one_chunk(c, in_range ? key_of(item) : -1, in_range);
         }
     }
 };

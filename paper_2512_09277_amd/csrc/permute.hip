@@ -29,8 +29,10 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const int32_t* __rest
     };
     OrderedCounter oc;
     oc.init(n, spr, s_hist, s_cnt);
+    int keys[OrderedCounter::kCached];
+    oc.load_keys(key_of, keys);
     __syncthreads();
-    oc.histogram(key_of);
+    oc.histogram(key_of, keys);
     __syncthreads();
     oc.prefix();
     __syncthreads();
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const int32_t* __rest
         }
     }
     __syncthreads();
-    oc.number(key_of, [&](int p, int l, int occ) {
+    oc.number(key_of, keys, [&](int p, int l, int occ) {
         int row = -1;
         if (l >= 0) {
             row = s_off[l] + occ;

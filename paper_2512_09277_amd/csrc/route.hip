@@ -58,6 +58,8 @@ __device__ __forceinline__ void build_host_masks(const int32_t* s2e, int N, int 
 }
 
 // ------------------------------------------------------------------------------------------ METRO
+constexpr int kIdCache = 8;      // int4 loads of ids a thread keeps in registers between the two passes
+
 __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     __shared__ int s_active[kMaxN];
     __shared__ uint32_t s_host_lo[kMaxN], s_host_hi[kMaxN];
@@ -76,6 +78,24 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     int32_t* pair_slot = a.pair_slot + (size_t)layer * n_pairs;
     const int tid = threadIdx.x;
 
+    // The global loads go out first, so that their latency overlaps the LDS set-up; the ids stay in
+    // registers for the emit pass (batches beyond kIdCache*4*1024 pairs re-read the rest).
+    const int4* v = reinterpret_cast<const int4*>(ids);
+    const int n4 = a.vec4 ? n_pairs / 4 : 0;
+    int4 idc[kIdCache];
+#pragma unroll
+    for (int c = 0; c < kIdCache; ++c) {
+        idc[c] = make_int4(-1, -1, -1, -1);
+        const int i = tid + c * kThreads;
+        if (i < n4) idc[c] = v[i];
+    }
+    int se[kMaxS / kThreads];
+#pragma unroll
+    for (int j = 0; j < kMaxS / kThreads; ++j) {
+        const int sl = tid + j * kThreads;
+        se[j] = sl < S ? s2e[sl] : -1;
+    }
+
     for (int e = tid; e < kMaxN; e += kThreads) {
         s_active[e] = 0;
         s_host_lo[e] = 0;
@@ -92,26 +112,29 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     if (tid == 0) s_err = 0;
     __syncthreads();
 
-    // T[i] > 0 for every expert: one coalesced pass over the ids.
-    build_host_masks(s2e, N, S, spr, s_host_lo, s_host_hi, &s_err);
-    if (a.vec4) {
-        const int4* v = reinterpret_cast<const int4*>(ids);
-        for (int i = tid; i < n_pairs / 4; i += kThreads) {
-            const int4 q = v[i];
-            const int four[4] = {q.x, q.y, q.z, q.w};
+    // Ranks hosting each expert (matrix A) and T[i] > 0 for every expert.
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (four[c] < -1 || four[c] >= N) atomicOr(&s_err, METRO_FLAG_BAD_ID);
-                else if (four[c] >= 0) s_active[four[c]] = 1;
-            }
-        }
-    } else {
-        for (int i = tid; i < n_pairs; i += kThreads) {
-            const int id = ids[i];
-            if (id < -1 || id >= N) atomicOr(&s_err, METRO_FLAG_BAD_ID);
-            else if (id >= 0) s_active[id] = 1;
+    for (int j = 0; j < kMaxS / kThreads; ++j) {
+        const int sl = tid + j * kThreads;
+        if (sl < S) {
+            if (se[j] < -1 || se[j] >= N) { atomicOr(&s_err, METRO_FLAG_BAD_PLACEMENT); se[j] = -1; }
+            else if (se[j] >= 0) set_bit64(s_host_lo, s_host_hi, se[j], sl / spr);
         }
     }
+    auto mark = [&](int id) {
+        if (id < -1 || id >= N) atomicOr(&s_err, METRO_FLAG_BAD_ID);
+        else if (id >= 0) s_active[id] = 1;
+    };
+#pragma unroll
+    for (int c = 0; c < kIdCache; ++c) {
+        mark(idc[c].x); mark(idc[c].y); mark(idc[c].z); mark(idc[c].w);   // padding (-1) where not loaded
+    }
+    for (int i = tid + kIdCache * kThreads; i < n4; i += kThreads) {
+        const int4 q = v[i];
+        mark(q.x); mark(q.y); mark(q.z); mark(q.w);
+    }
+    if (!a.vec4)
+        for (int i = tid; i < n_pairs; i += kThreads) mark(ids[i]);
     __syncthreads();
 
     // Split the active experts: single replica (forced) or several (the serial chain).
@@ -133,6 +156,8 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
 
     // The chain: wave 0, lane g keeps L[g].  Load of rank g when expert e is served =
     //   L (all experts of lower words) + forced experts of this word below e + chain picks of this word.
+    // Per 64-expert word the lanes first fetch the host masks of the word's experts (lane b <-> expert
+    // 64w+b), so that the serial loop reads them with readlane instead of waiting for LDS each step.
     if (tid < kWave) {
         const int g = tid;
         int L = 0;
@@ -141,15 +166,16 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
         const int n_words = (N + 63) >> 6;
         for (int w = 0; w < n_words; ++w) {
             const uint64_t forced = g < G ? join64(s_forced_lo[w][g], s_forced_hi[w][g]) : 0ull;
+            const int my_e = min((w << 6) + g, kMaxN - 1);
+            const uint32_t hl = s_host_lo[my_e], hh = s_host_hi[my_e];
             uint64_t multi = join64(__builtin_amdgcn_readfirstlane(s_multi_lo[w]),
                                     __builtin_amdgcn_readfirstlane(s_multi_hi[w]));
             int picked = 0;
+            uint32_t best_of = 0xffffffffu;              // lane b: rank chosen for expert 64w+b
             while (multi) {
                 const int b = __ffsll((unsigned long long)multi) - 1;
                 multi &= multi - 1;
-                const int e = (w << 6) + b;
-                uint64_t cand = join64(__builtin_amdgcn_readfirstlane(s_host_lo[e]),
-                                       __builtin_amdgcn_readfirstlane(s_host_hi[e]));
+                uint64_t cand = join64(__builtin_amdgcn_readlane(hl, b), __builtin_amdgcn_readlane(hh, b));
                 const int cur = L + __popcll(forced & ((1ull << b) - 1ull)) + picked;
                 for (int bit = load_bits - 1; bit >= 0; --bit) {     // keep the candidates with the smallest load
                     const uint64_t zero_here = __ballot(((cur >> bit) & 1) == 0) & cand;
@@ -157,17 +183,20 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
                 }
                 const int best = __ffsll((unsigned long long)cand) - 1;   // lowest rank among them
                 if (g == best) ++picked;
-                if (g == 0) s_rank[e] = best;
+                if (g == b) best_of = best;
             }
+            if (best_of != 0xffffffffu) s_rank[(w << 6) + g] = (int)best_of;
             L += __popcll(forced) + picked;
         }
     }
     __syncthreads();
 
     // y[i][g*] = 1 -> the lowest slot of expert i on rank g*.
-    for (int s = tid; s < S; s += kThreads) {
-        const int e = s2e[s];
-        if (e >= 0 && e < N && s_active[e] && s_rank[e] == s / spr) atomicMin(&s_slot[e], s);
+#pragma unroll
+    for (int j = 0; j < kMaxS / kThreads; ++j) {
+        const int sl = tid + j * kThreads;
+        const int e = se[j];
+        if (sl < S && e >= 0 && s_active[e] && s_rank[e] == sl / spr) atomicMin(&s_slot[e], sl);
     }
     __syncthreads();
     for (int e = tid; e < N; e += kThreads) {
@@ -186,24 +215,19 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     if (tid == 0) a.err_flag[layer] = s_err;
 
     // x from y: every pair of expert i goes to its activated replica.
-    if (a.vec4) {
-        const int4* v = reinterpret_cast<const int4*>(ids);
-        int4* o = reinterpret_cast<int4*>(pair_slot);
-        for (int i = tid; i < n_pairs / 4; i += kThreads) {
-            const int4 q = v[i];
-            int4 r;
-            r.x = (q.x >= 0 && q.x < N) ? s_slot[q.x] : -1;
-            r.y = (q.y >= 0 && q.y < N) ? s_slot[q.y] : -1;
-            r.z = (q.z >= 0 && q.z < N) ? s_slot[q.z] : -1;
-            r.w = (q.w >= 0 && q.w < N) ? s_slot[q.w] : -1;
-            o[i] = r;
-        }
-    } else {
-        for (int i = tid; i < n_pairs; i += kThreads) {
-            const int id = ids[i];
-            pair_slot[i] = (id >= 0 && id < N) ? s_slot[id] : -1;
-        }
+    auto slot_of = [&](int id) { return (id >= 0 && id < N) ? s_slot[id] : -1; };
+    int4* o = reinterpret_cast<int4*>(pair_slot);
+#pragma unroll
+    for (int c = 0; c < kIdCache; ++c) {
+        const int i = tid + c * kThreads;
+        if (i < n4) o[i] = make_int4(slot_of(idc[c].x), slot_of(idc[c].y), slot_of(idc[c].z), slot_of(idc[c].w));
     }
+    for (int i = tid + kIdCache * kThreads; i < n4; i += kThreads) {
+        const int4 q = v[i];
+        o[i] = make_int4(slot_of(q.x), slot_of(q.y), slot_of(q.z), slot_of(q.w));
+    }
+    if (!a.vec4)
+        for (int i = tid; i < n_pairs; i += kThreads) pair_slot[i] = slot_of(ids[i]);
 }
 
 // ------------------------------------------------------------------------------------------ token-balanced
@@ -243,7 +267,9 @@ __global__ __launch_bounds__(kThreads) void token_balanced_kernel(RouteArgs a) {
         if (id < -1 || id >= N) { atomicOr(&s_err, METRO_FLAG_BAD_ID); return -1; }
         return id;
     };
-    oc.histogram(key_of);
+    int keys[OrderedCounter::kCached];
+    oc.load_keys(key_of, keys);
+    oc.histogram(key_of, keys);
     __syncthreads();
     oc.prefix();                                     // s_cnt[e] = T[e]
 
@@ -290,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void token_balanced_kernel(RouteArgs a) {
             const int id = ids[p];
             return (id < 0 || id >= N) ? -1 : id;
         },
-        [&](int p, int e, int occ) {
+        keys, [&](int p, int e, int occ) {
             int slot = -1;
             if (e >= 0) {
                 const int r = s_base[e + 1] - s_base[e];
