@@ -62,7 +62,7 @@ class HotPath:
             nbytes = w13.numel() * w13.element_size() + w2.numel() * w2.element_size()
             n = max(1, -(-1536 * 2**20 // nbytes))
             def same_layout(t):
-                c = torch.empty_strided(t.size(), t.stride(), dtype=t.dtype, device=t.device)
+                c = self.torch.empty_strided(t.size(), t.stride(), dtype=t.dtype, device=t.device)
                 c.copy_(t)
                 return c
 

@@ -5,9 +5,9 @@
 // land directly in the matrix-core operand layout (16 rows x 64 contiguous bytes per instruction);
 // the small, heavily reused activations are staged through LDS.  Work is cut into tiles of one
 // slot's rows:
-//   stream tiles (<= 32 rows, the bulk of the bytes): per wave 2 x 16 weight rows, K steps of 128,
+//   stream tiles (<= 64 rows, the bulk of the bytes): per wave 2 x 16 weight rows, K steps of 128,
 //       loads issued two steps ahead so that ~128 KB per CU are in flight at 2 waves per SIMD;
-//   wide tiles (33..128 rows, the few popular experts): per wave 4 x 16 weight rows, K steps of 64,
+//   wide tiles (65..128 rows, the few popular experts): per wave 4 x 16 weight rows, K steps of 64,
 //       so that each activation fragment read from LDS feeds four MFMAs and the matrix cores,
 //       not LDS, bound the tile; they are listed first so that they spread over the chip early.
 //   gate/up: a wave owns gate rows and the matching up rows, so silu(gate)*up is formed in
@@ -33,7 +33,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kThreads = 256;
 constexpr int kMaxSpr = 64;
 constexpr int kWideRows = 128;              // rows of a full wide tile
-constexpr int kStreamRows = 32;             // a remainder of at most this many rows is a stream tile
+constexpr int kStreamRows = 64;             // largest remainder that may become a stream tile
 constexpr size_t kPlanBytes = 256;          // header before the tile list
 
 struct Tile {
@@ -48,10 +48,10 @@ __host__ __device__ inline int max_tiles(int cap, int spr) { return spr + cap / 
 
 // ------------------------------------------------------------------------------------------ plan
 // One wave, lane = local slot.  A slot of m rows gives m / 128 full wide tiles and one tile for the
-// remainder (wide if > 32 rows, else stream).  Order: full wide tiles, partial wide tiles by rows
+// remainder (wide if > 64 rows, else stream).  Order: full wide tiles, partial wide tiles by rows
 // descending, stream tiles by rows descending.
 __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ group_offsets, int spr, int cap,
-                                                     int tile_cap, PlanHeader* __restrict__ hdr,
+                                                     int tile_cap, int stream_rows, PlanHeader* __restrict__ hdr,
                                                      Tile* __restrict__ tiles) {
     const int l = threadIdx.x;
     int begin = 0, m = 0;
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         const int pj = __shfl(part, j);
         rank += (pj > part || (pj == part && j < l)) ? 1 : 0;
     }
-    const int n_part_wide = __popcll(__ballot(part > kStreamRows));
+    const int n_part_wide = __popcll(__ballot(part > stream_rows));
     const int n_part = __popcll(__ballot(part > 0));
     for (int f = 0; f < full; ++f)
         if (incl - full + f < tile_cap) tiles[incl - full + f] = Tile{l, begin + f * kWideRows, kWideRows, 0};
@@ -171,7 +171,8 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     constexpr int kPeriod = (DEPTH == 1) ? 2 : (DEPTH == 2) ? 6 : 12; // lcm(NW, DEPTH, 2)
     static_assert(DEPTH >= 1 && DEPTH <= 3, "prefetch distance");
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave index, kept in a scalar register
     const int r16 = lane & 15, q = lane >> 4;
     const int H = a.H, I = a.I;
     const int K = kGateUp ? H : I;
@@ -181,27 +182,32 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     const int cols_per_wave = kGateUp ? NB * 8 : NB * 16;
     const int col0 = nt * 4 * cols_per_wave + wv * cols_per_wave;     // first output column of the wave
 
-    // weight row of block b: gate/up pairs block b (gate) with block b + NB/2 (up)
-    const __bf16* wbase = a.w + (size_t)t.slot * (kGateUp ? (size_t)2 * I : (size_t)H) * a.ldw;
-    const char* pw[NB];
+    // Addresses are a uniform base (scalar registers) plus a 32-bit per-lane offset, which keeps the
+    // vector registers for data in flight.  Weight row of block b: gate/up pairs block b (gate) with
+    // block b + NB/2 (up).
+    const char* wslot = reinterpret_cast<const char*>(a.w) + (size_t)t.slot * (kGateUp ? 2 * I : H) * a.ldw * 2;
+    const uint32_t w_lane = (uint32_t)(r16 * a.ldw + q * 8) * 2u;
+    const char* pw[NB];                                               // uniform: first row of block b
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         int col = kGateUp ? col0 + (b % (NB / 2)) * 16 : col0 + b * 16;
         col = col < n_out ? col : n_out - 16;   // a block past the last column repeats the last block
-        const int row = (kGateUp && b >= NB / 2) ? I + col + r16 : col + r16;
-        pw[b] = reinterpret_cast<const char*>(wbase + (size_t)row * a.ldw) + q * 16;
+        const int row = (kGateUp && b >= NB / 2) ? I + col : col;
+        pw[b] = wslot + (size_t)row * a.ldw * 2;
     }
 
     // activation staging: thread (frow, fchunk) copies 16 bytes of rows frow, frow + kRowsPerPass, ...
+    // (the host only takes this path while every activation byte offset fits 32 bits)
     const int frow = tid / kChunks, fchunk = tid % kChunks;
-    const char* px[NP];
+    const char* xbase = reinterpret_cast<const char*>(a.src);
+    uint32_t x_lane[NP];
 #pragma unroll
     for (int pz = 0; pz < NP; ++pz) {
         int row = pz * kRowsPerPass + frow;
         row = row < t.rows ? row : t.rows - 1;  // rows past the tile repeat its last row
-        const size_t src_row = kGateUp ? (size_t)min(max(a.perm_pair[t.row0 + row] / a.k, 0), a.T - 1)
-                                       : (size_t)(t.row0 + row);
-        px[pz] = reinterpret_cast<const char*>(a.src + src_row * K) + fchunk * 16;
+        const uint32_t src_row = kGateUp ? (uint32_t)min(max(a.perm_pair[t.row0 + row] / a.k, 0), a.T - 1)
+                                         : (uint32_t)(t.row0 + row);
+        x_lane[pz] = src_row * (uint32_t)(K * 2) + fchunk * 16;
     }
     const int wr_off = frow * kLdsRow + fchunk * 16;
     const int rd_off = r16 * kLdsRow + q * 16;
@@ -221,12 +227,12 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
-                w[buf][b * NJ + j] = *reinterpret_cast<const u32x4*>(pw[b] + (size_t)step * (BK * 2) + j * 64);
+                w[buf][b * NJ + j] = *reinterpret_cast<const u32x4*>(pw[b] + (size_t)step * (BK * 2) + w_lane + j * 64);
     };
     auto load_x = [&](int set, int step) {
 #pragma unroll
         for (int pz = 0; pz < NP; ++pz)
-            xr[set][pz] = *reinterpret_cast<const u32x4*>(px[pz] + (size_t)step * (BK * 2));
+            xr[set][pz] = *reinterpret_cast<const u32x4*>(xbase + (size_t)step * (BK * 2) + x_lane[pz]);
     };
     auto park_x = [&](int set, int buf) {
 #pragma unroll
@@ -281,7 +287,7 @@ __device__ __forceinline__ void ffn_tile(const FfnArgs& a, const Tile t, const i
     store_tile<kGateUp, NB, MT>(a, t, acc, col0, n_out, mt_count, r16, q);
 }
 
-constexpr int kLdsStream = 2 * 32 * (128 * 2 + 16);
+constexpr int kLdsStream = 2 * 64 * (128 * 2 + 16);
 constexpr int kLdsWide = 2 * 128 * (64 * 2 + 16);
 constexpr int kLdsBytes = kLdsWide > kLdsStream ? kLdsWide : kLdsStream;
 
@@ -306,7 +312,8 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     const Tile t = a.tiles[n_wide + ti];
     const int nt = id - ti * a.nt_stream;
     if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, nt, lds);
-    else ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, nt, lds);
+    else if (t.rows <= 32) ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, nt, lds);
+    else ffn_tile<kGateUp, 2, 4, 128, 2>(a, t, nt, lds);
 }
 
 // ------------------------------------------------------------------------------------------ general path
@@ -389,6 +396,14 @@ inline bool mfma_shape(int H, int I, int dtype) {
     return dtype == METRO_DTYPE_BF16 && H % 128 == 0 && I % 128 == 0;
 }
 
+inline bool mfma_fits(int T, int k, int H, int I);
+inline bool use_mfma(int T, int k, int H, int I, int dtype) { return mfma_shape(H, I, dtype) && mfma_fits(T, k, H, I); }
+
+// The MFMA kernels address activations with 32-bit byte offsets.
+inline bool mfma_fits(int T, int k, int H, int I) {
+    return (uint64_t)T * H * 2 < (1ull << 32) && (uint64_t)T * k * I * 2 < (1ull << 32);
+}
+
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Workspace layout shared by the three stages: [header 256 B][tile list][act].
@@ -433,6 +448,14 @@ int enable_large_lds() {                            // opt in to > 64 KB of dyna
     return METRO_OK;
 }
 
+// Remainders of at most this many rows become stream tiles.  Small FFNs (short K loops) are bound
+// by the latency of their few wide workgroups, so they keep up to 64 rows on the deep-prefetch stream
+// path; at large shapes the stream path's narrower column tile costs more activation re-reads than
+// it saves, so only <= 32 rows go there.
+inline int stream_rows_for(int H, int I) {
+    return (size_t)H * I >= (size_t)4096 * 2048 ? 32 : kStreamRows;
+}
+
 inline int launched() { return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP; }
 
 }  // namespace
@@ -443,7 +466,7 @@ extern "C" size_t moe_grouped_ffn_workspace_bytes(int T, int k, int spr, int H, 
     if (T < 0 || k < 1 || spr < 1 || H < 1 || I < 1) return 0;
     const size_t cap = (size_t)T * k;
     const size_t plan = kPlanBytes + align256(sizeof(Tile) * (size_t)max_tiles((int)cap, spr));
-    const size_t act = align256(cap * I * (mfma_shape(H, I, dtype) ? 2 : 4));
+    const size_t act = align256(cap * I * (use_mfma(T, k, H, I, dtype) ? 2 : 4));
     return plan + act + 256;
 }
 
@@ -453,10 +476,10 @@ extern "C" int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, 
     const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
     if (rc != METRO_OK) return rc;
     const int cap = T * k;
-    if (cap == 0 || !mfma_shape(H, I, dtype)) return METRO_OK;    // the general kernels need no plan
+    if (cap == 0 || !use_mfma(T, k, H, I, dtype)) return METRO_OK;    // the general kernels need no plan
     const Workspace w = carve(ws, cap, spr);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kWave), 0, (hipStream_t)stream, group_offsets, spr, cap,
-                       w.tile_cap, w.hdr, w.tiles);
+                       w.tile_cap, stream_rows_for(H, I), w.hdr, w.tiles);
     return launched();
 }
 
@@ -472,7 +495,7 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
     const Workspace w = carve(ws, cap, spr);
-    if (!mfma_shape(H, I, dtype)) {
+    if (!use_mfma(T, k, H, I, dtype)) {
         const int per = kThreads / kWave;
         const dim3 grid(cap, (I + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
@@ -511,7 +534,7 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
     const Workspace w = carve(ws, cap, spr);
-    if (!mfma_shape(H, I, dtype)) {
+    if (!use_mfma(T, k, H, I, dtype)) {
         const int per = kThreads / kWave;
         const dim3 grid(cap, (H + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
