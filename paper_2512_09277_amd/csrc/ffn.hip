@@ -5,9 +5,9 @@
 // land directly in the matrix-core operand layout (16 rows x 64 contiguous bytes per instruction);
 // the small, heavily reused activations are staged through LDS.  Work is cut into tiles of one
 // slot's rows:
-//   stream tiles (<= 64 rows, the bulk of the bytes): per wave 2 x 16 weight rows, K steps of 128,
+//   stream tiles (<= 32 rows at large shapes, the bulk of the bytes): per wave 2 x 16 weight rows, K steps of 128,
 //       loads issued two steps ahead so that ~128 KB per CU are in flight at 2 waves per SIMD;
-//   wide tiles (65..128 rows, the few popular experts): per wave 4 x 16 weight rows, K steps of 64,
+//   wide tiles (33..128 rows at large shapes, the few popular experts): per wave 4 x 16 weight rows, K steps of 64,
 //       so that each activation fragment read from LDS feeds four MFMAs and the matrix cores,
 //       not LDS, bound the tile; they are listed first so that they spread over the chip early.
 //   gate/up: a wave owns gate rows and the matching up rows, so silu(gate)*up is formed in
@@ -33,7 +33,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kThreads = 256;
 constexpr int kMaxSpr = 64;
 constexpr int kWideRows = 128;              // rows of a full wide tile
-constexpr int kStreamRows = 64;             // largest remainder that may become a stream tile
+constexpr int kStreamRows = 128;            // largest remainder that may become a stream tile
 constexpr size_t kPlanBytes = 256;          // header before the tile list
 
 struct Tile {
@@ -48,7 +48,7 @@ __host__ __device__ inline int max_tiles(int cap, int spr) { return spr + cap / 
 
 // ------------------------------------------------------------------------------------------ plan
 // One wave, lane = local slot.  A slot of m rows gives m / 128 full wide tiles and one tile for the
-// remainder (wide if > 64 rows, else stream).  Order: full wide tiles, partial wide tiles by rows
+// remainder (wide if it has more than `stream_rows` rows, else stream).  Order: full wide tiles, partial wide tiles by rows
 // descending, stream tiles by rows descending.
 __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ group_offsets, int spr, int cap,
                                                      int tile_cap, int stream_rows, PlanHeader* __restrict__ hdr,
@@ -78,7 +78,8 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         if (incl - full + f < tile_cap) tiles[incl - full + f] = Tile{l, begin + f * kWideRows, kWideRows, 0};
     if (part > 0 && n_full + rank < tile_cap) tiles[n_full + rank] = Tile{l, begin + full * kWideRows, part, 0};
     if (l == 0) {
-        const int n_wide = min(n_full + n_part_wide, tile_cap);
+        // stream_rows >= kWideRows: no wide class at all, full tiles take the stream path too
+        const int n_wide = stream_rows >= kWideRows ? 0 : min(n_full + n_part_wide, tile_cap);
         hdr->n_wide = n_wide;
         hdr->n_stream = min(n_full + n_part, tile_cap) - n_wide;
     }
@@ -313,7 +314,8 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     const int nt = id - ti * a.nt_stream;
     if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, nt, lds);
     else if (t.rows <= 32) ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, nt, lds);
-    else ffn_tile<kGateUp, 2, 4, 128, 2>(a, t, nt, lds);
+    else if (t.rows <= 64) ffn_tile<kGateUp, 2, 4, 128, 2>(a, t, nt, lds);
+    else ffn_tile<kGateUp, 2, 8, 64, 3>(a, t, nt, lds);
 }
 
 // ------------------------------------------------------------------------------------------ general path
@@ -448,13 +450,12 @@ int enable_large_lds() {                            // opt in to > 64 KB of dyna
     return METRO_OK;
 }
 
-// Remainders of at most this many rows become stream tiles.  Small FFNs (short K loops) are bound
-// by the latency of their few wide workgroups, so they keep up to 64 rows on the deep-prefetch stream
-// path; at large shapes the stream path's narrower column tile costs more activation re-reads than
-// it saves, so only <= 32 rows go there.
-inline int stream_rows_for(int H, int I) {
-    return (size_t)H * I >= (size_t)4096 * 2048 ? 32 : kStreamRows;
-}
+// Remainders of at most this many rows become stream tiles.  A wide workgroup prefetches one step
+// ahead, so its K loop runs at about one memory latency per step: at large shapes that hides behind
+// the stream items, at small ones (short launches, HBM not saturated) it is the critical path.  Small
+// FFNs therefore keep every tile on the deep-prefetch stream path, whose narrower column tile costs
+// more activation re-reads -- which is what decides at large shapes, where only <= 32 rows go there.
+inline int stream_rows_for(int H, int I) { return (size_t)H * I >= (size_t)4096 * 2048 ? 32 : kStreamRows; }
 
 inline int launched() { return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP; }
 
