@@ -184,7 +184,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle FFN work")
     ap.add_argument("--dense-weights", action="store_true",
-                    help="weight rows back to back (default: rows of a multiple of 1024 bytes are padded by 128 "
+                    help="weight rows back to back (default: rows of a multiple of 4096 bytes are padded by 128 "
                          "elements, the layout the library recommends)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for rocprofv3 byte counters)")

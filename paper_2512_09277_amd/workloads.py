@@ -246,9 +246,9 @@ def device_activations(w: Workload, device, layer: int = 0, T: Optional[int] = N
 
 def padded_pitch(K: int, elt_bytes: int = 2) -> int:
     """Row pitch in elements for weight rows of K elements: rows whose byte length is a multiple of
-    1024 get 128 more elements, so that the rows one load instruction touches spread over the HBM
+    4096 get 128 more elements, so that the rows one load instruction touches spread over the HBM
     channels instead of piling onto a few of them."""
-    return K + 128 if (K * elt_bytes) % 1024 == 0 else K
+    return K + 128 if (K * elt_bytes) % 4096 == 0 else K
 
 
 def device_rank_share(wt, slot_to_expert: np.ndarray, g: int, spr: int, pad: bool = False):
