@@ -123,15 +123,13 @@ int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const int32_t* grou
                     void* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * The three stages of moe_grouped_ffn as separate calls, in the order plan -> gate_up -> down, on
- * the same workspace and stream (moe_grouped_ffn is exactly that sequence).  They exist so that a
- * caller can put events between the stages or overlap other work; arguments as above.
- *   plan     turns group_offsets into the work list of the two kernels
+ * The two stages of moe_grouped_ffn as separate calls, in the order gate_up -> down, on the same
+ * workspace and stream (moe_grouped_ffn is exactly that sequence).  They exist so that a caller can
+ * put events between the stages or overlap other work; arguments as above.  Both read
+ * group_offsets: every workgroup derives its own piece of work from it, there is no planning pass.
  *   gate_up  act = silu(x . w13[gate]^T) * (x . w13[up]^T), kept in the workspace
  *   down     y_perm = act . w2^T
  */
-int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype, void* ws,
-                         size_t ws_bytes, void* stream);
 int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
                             int spr, int H, int I, int dtype, const void* w13, int ldw13, void* ws,
                             size_t ws_bytes, void* stream);

@@ -21,7 +21,7 @@ FLAG_BAD_ID, FLAG_NO_REPLICA, FLAG_BAD_PLACEMENT = 1, 2, 4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ("metro_status_string", "metro_route", "metro_route_token_balanced", "moe_permute",
-           "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_plan", "moe_grouped_ffn_gate_up",
+           "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gate_up",
            "moe_grouped_ffn_down", "moe_unpermute")
 
 
@@ -52,8 +52,6 @@ def load() -> ctypes.CDLL:
         lib.moe_grouped_ffn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
         lib.moe_grouped_ffn.restype = ci
         lib.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, ci, vp, vp, sz, vp]
-        lib.moe_grouped_ffn_plan.restype = ci
-        lib.moe_grouped_ffn_plan.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
         lib.moe_grouped_ffn_gate_up.restype = ci
         lib.moe_grouped_ffn_gate_up.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, sz, vp]
         lib.moe_grouped_ffn_down.restype = ci
@@ -197,7 +195,7 @@ def moe_grouped_ffn(x: torch.Tensor, perm_pair: torch.Tensor, group_offsets: tor
 
 
 def moe_grouped_ffn_stages(x, perm_pair, group_offsets, k: int, w13, w2, y_perm, ws, between=None):
-    """moe_grouped_ffn as its three stage calls; `between(i)` (i = 0..3) is called before, between and
+    """moe_grouped_ffn as its two stage calls; `between(i)` (i = 0..2) is called before, between and
     after the stages, e.g. to record events on the current stream."""
     T, H = x.shape
     spr, two_i, _ = w13.shape
@@ -207,17 +205,15 @@ def moe_grouped_ffn_stages(x, perm_pair, group_offsets, k: int, w13, w2, y_perm,
     go = _dev(group_offsets, torch.int32, "group_offsets")
     wsp, wsn = _dev(ws, torch.uint8, "ws"), ws.numel()
     mark = between if between is not None else (lambda i: None)
-    mark(0)
-    _check(lib.moe_grouped_ffn_plan(go, T, k, spr, H, I, code, wsp, wsn, _stream()))
     p13, ld13 = _weights(w13, x.dtype, "w13")
     p2, ld2 = _weights(w2, x.dtype, "w2")
-    mark(1)
+    mark(0)
     _check(lib.moe_grouped_ffn_gate_up(_dev(x, x.dtype, "x"), _dev(perm_pair, torch.int32, "perm_pair"), go, T, k,
                                        spr, H, I, code, p13, ld13, wsp, wsn, _stream()))
-    mark(2)
+    mark(1)
     _check(lib.moe_grouped_ffn_down(go, T, k, spr, H, I, code, p2, ld2, _dev(y_perm, x.dtype, "y_perm"), wsp, wsn,
                                     _stream()))
-    mark(3)
+    mark(2)
     return y_perm
 
 

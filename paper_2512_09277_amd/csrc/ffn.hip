@@ -29,31 +29,35 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kMaxSpr = 64;
 constexpr int kWideRows = 128;              // rows of a full wide tile
 constexpr int kStreamRows = 128;            // largest remainder that may become a stream tile
-constexpr size_t kPlanBytes = 256;          // header before the tile list
 
 struct Tile {
-    int slot, row0, rows, pad;
-};
-
-struct PlanHeader {
-    int n_wide, n_stream;                   // tiles[0, n_wide) wide, then n_stream stream tiles
+    int slot, row0, rows, col;              // rows [row0, row0 + rows) of a slot x column tile `col`
 };
 
 __host__ __device__ inline int max_tiles(int cap, int spr) { return spr + cap / kWideRows; }
 
-// ------------------------------------------------------------------------------------------ plan
-// One wave, lane = local slot.  A slot of m rows gives m / 128 full wide tiles and one tile for the
-// remainder (wide if it has more than `stream_rows` rows, else stream).  Order: full wide tiles, partial wide tiles by rows
-// descending, stream tiles by rows descending.
-__global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ group_offsets, int spr, int cap,
-                                                     int tile_cap, int stream_rows, PlanHeader* __restrict__ hdr,
-                                                     Tile* __restrict__ tiles) {
-    const int l = threadIdx.x;
+// ------------------------------------------------------------------------------------------ work items
+// A slot of m rows gives m / 128 full tiles and one tile for the remainder; a tile is wide if it has
+// more than `stream_rows` rows.  Tile order: full tiles, then the remainders by rows descending
+// (ties: lower slot first); the first n_wide of them are the wide ones.  Work item = (tile, column
+// tile), tile-major, wide items first, `ntw` column tiles per wide tile and `nts` per stream tile.
+// Every workgroup derives its own item from group_offsets (65 integers, one memory round trip, a few
+// hundred scalar-ish instructions): no planning kernel, no list in memory.  Each wave computes the
+// same result with lane = local slot; everything returned is uniform.
+struct Item {
+    Tile tile;
+    bool valid, wide;
+};
+
+__device__ __forceinline__ Item locate_item(const int32_t* __restrict__ group_offsets, int spr, int cap,
+                                            int stream_rows, int ntw, int nts, int id) {
+    const int l = lane_id();
     int begin = 0, m = 0;
     if (l < spr) {                              // offsets that are not a partition of [0, cap] are clamped
         begin = min(max(group_offsets[l], 0), cap);
@@ -66,23 +70,45 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         const int up = __shfl_up(incl, d);
         if (l >= d) incl += up;
     }
-    const int n_full = __shfl(incl, kWave - 1);
+    const int n_full = __builtin_amdgcn_readlane(incl, kWave - 1);
     int rank = 0;                               // remainders: more rows first, then lower slot
+#pragma unroll
     for (int j = 0; j < kWave; ++j) {
-        const int pj = __shfl(part, j);
+        const int pj = __builtin_amdgcn_readlane(part, j);
         rank += (pj > part || (pj == part && j < l)) ? 1 : 0;
     }
     const int n_part_wide = __popcll(__ballot(part > stream_rows));
     const int n_part = __popcll(__ballot(part > 0));
-    for (int f = 0; f < full; ++f)
-        if (incl - full + f < tile_cap) tiles[incl - full + f] = Tile{l, begin + f * kWideRows, kWideRows, 0};
-    if (part > 0 && n_full + rank < tile_cap) tiles[n_full + rank] = Tile{l, begin + full * kWideRows, part, 0};
-    if (l == 0) {
-        // stream_rows >= kWideRows: no wide class at all, full tiles take the stream path too
-        const int n_wide = stream_rows >= kWideRows ? 0 : min(n_full + n_part_wide, tile_cap);
-        hdr->n_wide = n_wide;
-        hdr->n_stream = min(n_full + n_part, tile_cap) - n_wide;
+    // stream_rows >= 128: no wide class at all, full tiles take the stream path too
+    const int n_wide = stream_rows >= kWideRows ? 0 : n_full + n_part_wide;
+    const int n_stream = n_full + n_part - n_wide;
+    const int wide_items = n_wide * ntw, n_items = wide_items + n_stream * nts;
+
+    Item it;
+    it.valid = id < n_items;
+    it.wide = id < wide_items;
+    it.tile = Tile{0, 0, 0, 0};
+    if (!it.valid) return it;
+    const int nt = it.wide ? ntw : nts, r = it.wide ? id : id - wide_items;
+    const int tl = r / nt;
+    const int ti = it.wide ? tl : n_wide + tl;
+    it.tile.col = r - tl * nt;
+    if (ti < n_full) {
+        const uint64_t owner = __ballot(incl - full <= ti && ti < incl);      // exactly one lane
+        const int o = __ffsll((unsigned long long)owner) - 1;
+        const int first = __builtin_amdgcn_readlane(incl - full, o);
+        it.tile.slot = o;
+        it.tile.row0 = __builtin_amdgcn_readlane(begin, o) + (ti - first) * kWideRows;
+        it.tile.rows = kWideRows;
+    } else {
+        const uint64_t owner = __ballot(part > 0 && n_full + rank == ti);     // exactly one lane
+        const int o = __ffsll((unsigned long long)owner) - 1;
+        it.tile.slot = o;
+        it.tile.row0 = __builtin_amdgcn_readlane(begin + full * kWideRows, o);
+        it.tile.rows = __builtin_amdgcn_readlane(part, o);
     }
+    it.valid = it.tile.rows > 0;                // always true here; keeps a broken invariant from indexing row -1
+    return it;
 }
 
 // ------------------------------------------------------------------------------------------ MFMA path
@@ -91,11 +117,11 @@ struct FfnArgs {
     const int32_t* perm_pair; // gate/up only
     const __bf16* w;          // gate/up: w13[spr,2I,H]; down: w2[spr,H,I]
     __bf16* dst;              // gate/up: act[cap,I]; down: y_perm[cap,H]
-    const PlanHeader* hdr;
-    const Tile* tiles;
-    int T, k, H, I;
+    const int32_t* group_offsets;
+    int T, k, spr, H, I;
     int ldw;                  // elements between consecutive weight rows (>= K)
-    int nt_wide, nt_stream;   // workgroups per wide / stream tile
+    int stream_rows;          // tiles with more rows are wide
+    int ntw, nts;             // column tiles per wide / stream tile
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -295,27 +321,19 @@ constexpr int kLdsBytes = kLdsWide > kLdsStream ? kLdsWide : kLdsStream;
 template <bool kGateUp>
 __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int n_wide = a.hdr->n_wide, n_stream = a.hdr->n_stream;
-    // Work items = (tile, column tile), wide tiles first: a wide workgroup lives several times longer
+    // Work items = (tile, column tile), wide items first: a wide workgroup lives several times longer
     // than a stream one, so it has to start early for the stream items to fill in around it.
-    // (Measured alternatives that lost: spreading the wide items through the launch order, and
-    // alternating wide and stream items.)  Everything here is uniform per workgroup.
-    int id = blockIdx.x;
-    const int wide_items = n_wide * a.nt_wide;
-    if (id < wide_items) {
-        const int ti = id / a.nt_wide;
-        ffn_tile<kGateUp, 4, 8, 64, 1>(a, a.tiles[ti], id - ti * a.nt_wide, lds);
-        return;
-    }
-    id -= wide_items;
-    const int ti = id / a.nt_stream;
-    if (ti >= n_stream) return;
-    const Tile t = a.tiles[n_wide + ti];
-    const int nt = id - ti * a.nt_stream;
-    if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, nt, lds);
-    else if (t.rows <= 32) ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, nt, lds);
-    else if (t.rows <= 64) ffn_tile<kGateUp, 2, 4, 128, 2>(a, t, nt, lds);
-    else ffn_tile<kGateUp, 2, 8, 64, 3>(a, t, nt, lds);
+    // (Measured alternatives that lost: spreading the wide items through the launch order,
+    // alternating wide and stream items, and per-XCD work queues.)  Everything here is uniform per
+    // workgroup.
+    const Item it = locate_item(a.group_offsets, a.spr, a.T * a.k, a.stream_rows, a.ntw, a.nts, blockIdx.x);
+    if (!it.valid) return;
+    const Tile t = it.tile;
+    if (it.wide) ffn_tile<kGateUp, 4, 8, 64, 1>(a, t, t.col, lds);
+    else if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 128, 2>(a, t, t.col, lds);
+    else if (t.rows <= 32) ffn_tile<kGateUp, 2, 2, 128, 2>(a, t, t.col, lds);
+    else if (t.rows <= 64) ffn_tile<kGateUp, 2, 4, 128, 2>(a, t, t.col, lds);
+    else ffn_tile<kGateUp, 2, 8, 64, 3>(a, t, t.col, lds);
 }
 
 // ------------------------------------------------------------------------------------------ general path
@@ -408,23 +426,8 @@ inline bool mfma_fits(int T, int k, int H, int I) {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// Workspace layout shared by the three stages: [header 256 B][tile list][act].
-struct Workspace {
-    PlanHeader* hdr;
-    Tile* tiles;
-    char* act;
-    int tile_cap;
-};
-
-inline Workspace carve(void* ws, int cap, int spr) {
-    Workspace w;
-    char* base = (char*)ws;
-    w.hdr = (PlanHeader*)base;
-    w.tiles = (Tile*)(base + kPlanBytes);
-    w.tile_cap = max_tiles(cap, spr);
-    w.act = base + kPlanBytes + align256(sizeof(Tile) * (size_t)w.tile_cap);
-    return w;
-}
+// Workspace: the activations between the two stages, act[cap, I] (bf16 on the MFMA path, else f32).
+inline char* act_of(void* ws) { return (char*)ws; }
 
 int check_common(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype, const void* ws,
                  size_t ws_bytes) {
@@ -466,22 +469,8 @@ extern "C" size_t moe_grouped_ffn_workspace_bytes(int T, int k, int spr, int H, 
     using namespace metro;
     if (T < 0 || k < 1 || spr < 1 || H < 1 || I < 1) return 0;
     const size_t cap = (size_t)T * k;
-    const size_t plan = kPlanBytes + align256(sizeof(Tile) * (size_t)max_tiles((int)cap, spr));
     const size_t act = align256(cap * I * (use_mfma(T, k, H, I, dtype) ? 2 : 4));
-    return plan + act + 256;
-}
-
-extern "C" int moe_grouped_ffn_plan(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
-                                    void* ws, size_t ws_bytes, void* stream) {
-    using namespace metro;
-    const int rc = check_common(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes);
-    if (rc != METRO_OK) return rc;
-    const int cap = T * k;
-    if (cap == 0 || !use_mfma(T, k, H, I, dtype)) return METRO_OK;    // the general kernels need no plan
-    const Workspace w = carve(ws, cap, spr);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kWave), 0, (hipStream_t)stream, group_offsets, spr, cap,
-                       w.tile_cap, stream_rows_for(H, I), w.hdr, w.tiles);
-    return launched();
+    return act + 256;
 }
 
 extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T,
@@ -495,16 +484,16 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     const int cap = T * k;
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
-    const Workspace w = carve(ws, cap, spr);
+    char* act = act_of(ws);
     if (!use_mfma(T, k, H, I, dtype)) {
         const int per = kThreads / kWave;
         const dim3 grid(cap, (I + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
             hipLaunchKernelGGL(general_gate_up_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x,
-                               perm_pair, group_offsets, T, k, spr, H, I, (const float*)w13, ldw13, (float*)w.act);
+                               perm_pair, group_offsets, T, k, spr, H, I, (const float*)w13, ldw13, (float*)act);
         else
             hipLaunchKernelGGL(general_gate_up_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const __bf16*)x,
-                               perm_pair, group_offsets, T, k, spr, H, I, (const __bf16*)w13, ldw13, (float*)w.act);
+                               perm_pair, group_offsets, T, k, spr, H, I, (const __bf16*)w13, ldw13, (float*)act);
         return launched();
     }
     if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
@@ -513,13 +502,13 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     a.perm_pair = perm_pair;
     a.w = (const __bf16*)w13;
     a.ldw = ldw13;
-    a.dst = (__bf16*)w.act;
-    a.hdr = w.hdr;
-    a.tiles = w.tiles;
-    a.T = T; a.k = k; a.H = H; a.I = I;
-    a.nt_wide = I / 128;
-    a.nt_stream = I / 64;
-    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(w.tile_cap * a.nt_stream), dim3(kThreads), kLdsBytes, st, a);
+    a.dst = (__bf16*)act;
+    a.group_offsets = group_offsets;
+    a.T = T; a.k = k; a.spr = spr; a.H = H; a.I = I;
+    a.stream_rows = stream_rows_for(H, I);
+    a.ntw = I / 128;
+    a.nts = I / 64;
+    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(max_tiles(cap, spr) * a.nts), dim3(kThreads), kLdsBytes, st, a);
     return launched();
 }
 
@@ -534,31 +523,31 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     const int cap = T * k;
     if (cap == 0) return METRO_OK;
     hipStream_t st = (hipStream_t)stream;
-    const Workspace w = carve(ws, cap, spr);
+    char* act = act_of(ws);
     if (!use_mfma(T, k, H, I, dtype)) {
         const int per = kThreads / kWave;
         const dim3 grid(cap, (H + per - 1) / per);
         if (dtype == METRO_DTYPE_F32)
-            hipLaunchKernelGGL(general_down_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)w.act,
+            hipLaunchKernelGGL(general_down_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)act,
                                group_offsets, spr, H, I, (const float*)w2, ldw2, (float*)y_perm);
         else
-            hipLaunchKernelGGL(general_down_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const float*)w.act,
+            hipLaunchKernelGGL(general_down_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const float*)act,
                                group_offsets, spr, H, I, (const __bf16*)w2, ldw2, (__bf16*)y_perm);
         return launched();
     }
     if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
     FfnArgs a;
-    a.src = (const __bf16*)w.act;
+    a.src = (const __bf16*)act;
     a.perm_pair = nullptr;
     a.w = (const __bf16*)w2;
     a.ldw = ldw2;
     a.dst = (__bf16*)y_perm;
-    a.hdr = w.hdr;
-    a.tiles = w.tiles;
-    a.T = T; a.k = k; a.H = H; a.I = I;
-    a.nt_wide = (H + 255) / 256;
-    a.nt_stream = H / 128;
-    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(w.tile_cap * a.nt_stream), dim3(kThreads), kLdsBytes, st, a);
+    a.group_offsets = group_offsets;
+    a.T = T; a.k = k; a.spr = spr; a.H = H; a.I = I;
+    a.stream_rows = stream_rows_for(H, I);
+    a.ntw = (H + 255) / 256;
+    a.nts = H / 128;
+    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(max_tiles(cap, spr) * a.nts), dim3(kThreads), kLdsBytes, st, a);
     return launched();
 }
 
@@ -569,9 +558,7 @@ extern "C" int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const in
     if (!x || !perm_pair || !w13 || !w2 || !y_perm) return METRO_ERR_INVALID_ARG;
     if ((((uintptr_t)x | (uintptr_t)w13 | (uintptr_t)w2 | (uintptr_t)y_perm) & 15) != 0) return METRO_ERR_INVALID_ARG;
     if (ldw13 < H || ldw2 < I || ldw13 % 8 != 0 || ldw2 % 8 != 0) return METRO_ERR_INVALID_ARG;
-    int rc = moe_grouped_ffn_plan(group_offsets, T, k, spr, H, I, dtype, ws, ws_bytes, stream);
-    if (rc == METRO_OK)
-        rc = moe_grouped_ffn_gate_up(x, perm_pair, group_offsets, T, k, spr, H, I, dtype, w13, ldw13, ws, ws_bytes,
+    int rc = moe_grouped_ffn_gate_up(x, perm_pair, group_offsets, T, k, spr, H, I, dtype, w13, ldw13, ws, ws_bytes,
                                      stream);
     if (rc == METRO_OK)
         rc = moe_grouped_ffn_down(group_offsets, T, k, spr, H, I, dtype, w2, ldw2, y_perm, ws, ws_bytes, stream);

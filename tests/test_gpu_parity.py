@@ -185,13 +185,26 @@ def test_permute_edge_cases(api, oracle):
 
 
 # ----------------------------------------------------------------------------- FFN + combine
+def ffn_call(api, x, perm_pair, group_offsets, k, w13, w2):
+    """moe_grouped_ffn into an output and a workspace pre-filled with 0xFF bytes (NaN in bf16 and
+    f32): a row the kernels skip cannot pass on values left behind by an earlier call."""
+    import torch
+
+    T, H = x.shape
+    spr, I = w13.shape[0], w13.shape[1] // 2
+    y = torch.full((T * k, H), float("nan"), dtype=x.dtype, device=x.device)
+    ws = torch.full((api.moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, x.dtype),), 0xFF, dtype=torch.uint8,
+                    device=x.device)
+    return api.moe_grouped_ffn(x, perm_pair, group_offsets, k, w13, w2, y_perm=y, ws=ws)
+
+
 def run_rank(api, oracle, x, w13, w2, tw, ps, g, spr, k, tol, rows=None):
     """One rank end to end on the GPU (permute -> FFN -> unpermute) against the oracle."""
     d_ps = dev_i32(ps)
     pm = api.moe_permute(d_ps, g, spr)
     ref_pm = oracle.permute(ps, g, spr)
     n = ref_pm["n_pairs"]
-    y = api.moe_grouped_ffn(dev_fp(x), pm["perm_pair"], pm["group_offsets"], k, dev_fp(w13), dev_fp(w2))
+    y = ffn_call(api, dev_fp(x), pm["perm_pair"], pm["group_offsets"], k, dev_fp(w13), dev_fp(w2))
     out = api.moe_unpermute(y, pm["pair_row"], dev_fp(tw))
     ref_y = oracle.ffn(x, ref_pm["perm_pair"], ref_pm["group_offsets"], k, w13, w2, rows=rows)
     got_y = host_f64(y)[:n] if rows is None else host_f64(y)[np.asarray(rows)]
@@ -281,10 +294,75 @@ def test_padded_weight_rows(api, oracle, dtype, H, I, tol):
         return view
 
     pm = api.moe_permute(dev_i32(ps), 0, spr)
-    y = api.moe_grouped_ffn(dev_fp(x), pm["perm_pair"], pm["group_offsets"], k, padded(w13, 128), padded(w2, 64))
+    y = ffn_call(api, dev_fp(x), pm["perm_pair"], pm["group_offsets"], k, padded(w13, 128), padded(w2, 64))
     ref_pm = oracle.permute(ps, 0, spr)
     ref = oracle.ffn(x, ref_pm["perm_pair"], ref_pm["group_offsets"], k, w13, w2)
     assert rel_err(host_f64(y)[:ref_pm["n_pairs"]], ref) <= tol
+
+
+def test_wide_and_stream_tiles_large_shape(api, oracle):
+    """H*I large enough that groups above 32 rows take the wide tiles: a several-tile group with a
+    wide and one with a narrow remainder, one-tile wide groups, narrow groups, an empty slot; every
+    row is compared."""
+    H, I, k, T = 4096, 2048, 4, 256
+    sizes = [300, 40, 0, 20, 128, 33, 1, 129 + 128, 32]
+    spr = len(sizes)
+    rng = np.random.default_rng(5)
+    pairs = rng.permutation(T * k)[:sum(sizes)]
+    ps = np.full(T * k, -1, np.int32)
+    at = 0
+    for l, m in enumerate(sizes):
+        ps[pairs[at:at + m]] = l
+        at += m
+    ps = ps.reshape(T, k)
+    x = W.activations(T, H, 15, "bf16")
+    w13, w2 = W.expert_weights(spr, H, I, 16, "bf16")
+    tw = W.gating_weights(T, k, 17)
+    print("wide + stream tiles, H=4096 I=2048", flush=True)
+    run_rank(api, oracle, x, w13, w2, tw, ps, 0, spr, k, BF16_TOL)
+
+
+def test_ffn_stage_calls_and_workspace_reuse(api, oracle):
+    """The two stage calls (gate_up, down) equal the whole call, and a workspace can be used again
+    without being cleared: the same rows come out on every pass."""
+    import torch
+
+    H, I, k, T = 512, 256, 4, 200
+    sizes = [17, 0, 1, 300, 16, 33, 129, 15, 64]
+    spr = len(sizes)
+    rng = np.random.default_rng(78)
+    pairs = rng.permutation(T * k)[:sum(sizes)]
+    ps = np.full(T * k, -1, np.int32)
+    at = 0
+    for l, m in enumerate(sizes):
+        ps[pairs[at:at + m]] = l
+        at += m
+    ps = ps.reshape(T, k)
+    x = dev_fp(W.activations(T, H, 5, "bf16"))
+    w13h, w2h = W.expert_weights(spr, H, I, 6, "bf16")
+    w13, w2 = dev_fp(w13h), dev_fp(w2h)
+    pm = api.moe_permute(dev_i32(ps), 0, spr)
+    ref_pm = oracle.permute(ps, 0, spr)
+    n = ref_pm["n_pairs"]
+    ref = oracle.ffn(W.activations(T, H, 5, "bf16"), ref_pm["perm_pair"], ref_pm["group_offsets"], k, w13h, w2h)
+    ws = torch.full((api.moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, torch.bfloat16),), 0xFF, dtype=torch.uint8,
+                    device="cuda")
+    y = torch.empty((T * k, H), dtype=torch.bfloat16, device="cuda")
+    lib, st = api.load(), api._stream()
+    args = (T, k, spr, H, I, api.DTYPE_BF16)
+    go, pp = pm["group_offsets"], pm["perm_pair"]
+    for _ in range(3):                                   # stage calls, same workspace
+        y.fill_(float("nan"))
+        assert lib.moe_grouped_ffn_gate_up(x.data_ptr(), pp.data_ptr(), go.data_ptr(), *args, w13.data_ptr(), H,
+                                           ws.data_ptr(), ws.numel(), st) == 0
+        assert lib.moe_grouped_ffn_down(go.data_ptr(), *args, w2.data_ptr(), I, y.data_ptr(), ws.data_ptr(),
+                                        ws.numel(), st) == 0
+        torch.cuda.synchronize()
+        assert rel_err(host_f64(y)[:n], ref) <= BF16_TOL
+    for _ in range(2):                                   # whole call, same workspace
+        y.fill_(float("nan"))
+        api.moe_grouped_ffn(x, pp, go, k, w13, w2, y_perm=y, ws=ws)
+        assert rel_err(host_f64(y)[:n], ref) <= BF16_TOL
 
 
 def test_empty_rank_ffn(api):
@@ -325,9 +403,10 @@ def test_full_size_sampled_rows(api, oracle, w):
     x = W.device_activations(w, "cuda")
     tw = W.gating_weights(w.T, w.k, w.seed(0, 4))
     pm = api.moe_permute(out["pair_slot"][0], g, w.spr)
-    y = api.moe_grouped_ffn(x, pm["perm_pair"], pm["group_offsets"], w.k, w13, w2)
+    y = ffn_call(api, x, pm["perm_pair"], pm["group_offsets"], w.k, w13, w2)
     res = api.moe_unpermute(y, pm["pair_row"], dev_fp(tw))
     torch.cuda.synchronize()
+    assert not torch.isnan(y[:int(pm["n_pairs"].item())]).any(), "a row of the rank was not computed"
     ref_pm = oracle.permute(ps, g, w.spr)
     go = ref_pm["group_offsets"]
     assert np.array_equal(pm["group_offsets"].cpu().numpy(), go)
