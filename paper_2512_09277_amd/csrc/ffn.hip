@@ -40,7 +40,7 @@ struct Tile {
     int slot, row0, rows, col;              // rows [row0, row0 + rows) of a slot x column tile `col`
 };
 
-__host__ __device__ inline int max_tiles(int cap, int spr) { return spr + cap / kWideRows; }
+__host__ __device__ inline int max_tiles(int cap, int spr, int tile_rows) { return spr + cap / tile_rows; }
 
 // ------------------------------------------------------------------------------------------ work items
 // A slot of m rows gives m / 128 full tiles and one tile for the remainder; a tile is wide if it has
@@ -56,14 +56,14 @@ struct Item {
 };
 
 __device__ __forceinline__ Item locate_item(const int32_t* __restrict__ group_offsets, int spr, int cap,
-                                            int stream_rows, int ntw, int nts, int id) {
+                                            int tile_rows, int stream_rows, int ntw, int nts, int id) {
     const int l = lane_id();
     int begin = 0, m = 0;
     if (l < spr) {                              // offsets that are not a partition of [0, cap] are clamped
         begin = min(max(group_offsets[l], 0), cap);
         m = min(max(group_offsets[l + 1], begin), cap) - begin;
     }
-    const int full = m / kWideRows, part = m % kWideRows;
+    const int full = m / tile_rows, part = m % tile_rows;
     int incl = full;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -80,7 +80,7 @@ __device__ __forceinline__ Item locate_item(const int32_t* __restrict__ group_of
     const int n_part_wide = __popcll(__ballot(part > stream_rows));
     const int n_part = __popcll(__ballot(part > 0));
     // stream_rows >= 128: no wide class at all, full tiles take the stream path too
-    const int n_wide = stream_rows >= kWideRows ? 0 : n_full + n_part_wide;
+    const int n_wide = stream_rows >= tile_rows ? 0 : n_full + n_part_wide;
     const int n_stream = n_full + n_part - n_wide;
     const int wide_items = n_wide * ntw, n_items = wide_items + n_stream * nts;
 
@@ -98,13 +98,13 @@ __device__ __forceinline__ Item locate_item(const int32_t* __restrict__ group_of
         const int o = __ffsll((unsigned long long)owner) - 1;
         const int first = __builtin_amdgcn_readlane(incl - full, o);
         it.tile.slot = o;
-        it.tile.row0 = __builtin_amdgcn_readlane(begin, o) + (ti - first) * kWideRows;
-        it.tile.rows = kWideRows;
+        it.tile.row0 = __builtin_amdgcn_readlane(begin, o) + (ti - first) * tile_rows;
+        it.tile.rows = tile_rows;
     } else {
         const uint64_t owner = __ballot(part > 0 && n_full + rank == ti);     // exactly one lane
         const int o = __ffsll((unsigned long long)owner) - 1;
         it.tile.slot = o;
-        it.tile.row0 = __builtin_amdgcn_readlane(begin + full * kWideRows, o);
+        it.tile.row0 = __builtin_amdgcn_readlane(begin + full * tile_rows, o);
         it.tile.rows = __builtin_amdgcn_readlane(part, o);
     }
     it.valid = it.tile.rows > 0;                // always true here; keeps a broken invariant from indexing row -1
@@ -120,6 +120,7 @@ struct FfnArgs {
     const int32_t* group_offsets;
     int T, k, spr, H, I;
     int ldw;                  // elements between consecutive weight rows (>= K)
+    int tile_rows;            // rows of a full tile (<= 128)
     int stream_rows;          // tiles with more rows are wide
     int ntw, nts;             // column tiles per wide / stream tile
 };
@@ -177,7 +178,8 @@ __device__ __forceinline__ void run_steps(std::integer_sequence<int, Us...>, F& 
 }
 template <int... Us, typename F>
 __device__ __forceinline__ void run_steps_tail(std::integer_sequence<int, Us...>, F& f, int s0, int n_steps) {
-    ((s0 + Us < n_steps ? f(std::integral_constant<int, Us>{}, s0 + Us) : void()), ...);
+    // short-circuit: once a step is past the end nothing after it is tested, the paths join only at the end
+    (void)((s0 + Us < n_steps && (f(std::integral_constant<int, Us>{}, s0 + Us), true)) && ...);
 }
 
 // One tile x one column tile.
@@ -326,7 +328,7 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     // (Measured alternatives that lost: spreading the wide items through the launch order,
     // alternating wide and stream items, and per-XCD work queues.)  Everything here is uniform per
     // workgroup.
-    const Item it = locate_item(a.group_offsets, a.spr, a.T * a.k, a.stream_rows, a.ntw, a.nts, blockIdx.x);
+    const Item it = locate_item(a.group_offsets, a.spr, a.T * a.k, a.tile_rows, a.stream_rows, a.ntw, a.nts, blockIdx.x);
     if (!it.valid) return;
     const Tile t = it.tile;
     if (it.wide) ffn_tile<kGateUp, 4, 8, 64, 1>(a, t, t.col, lds);
@@ -460,6 +462,13 @@ int enable_large_lds() {                            // opt in to > 64 KB of dyna
 // more activation re-reads -- which is what decides at large shapes, where only <= 32 rows go there.
 inline int stream_rows_for(int H, int I) { return (size_t)H * I >= (size_t)4096 * 2048 ? 32 : kStreamRows; }
 
+// Rows of a full tile.  128 amortises a slot's weights over the most rows (one HBM pass per 128 rows).
+// The smallest FFNs finish in a few tens of microseconds and are bound by their longest workgroup, not
+// by bytes: a 128-row tile spends longer in its matrix instructions than the whole launch should take,
+// while re-reading a small slot's weights from L2 is cheap, so they cut groups into 32-row tiles
+// (Qwen3-30B-shaped METRO rank: 60 -> 52 us; at 4096 x 1536 the same cut loses, 194 -> 250 us).
+inline int tile_rows_for(int H, int I) { return (size_t)H * I < (size_t)2048 * 1024 ? 32 : kWideRows; }
+
 inline int launched() { return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP; }
 
 }  // namespace
@@ -506,9 +515,10 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     a.group_offsets = group_offsets;
     a.T = T; a.k = k; a.spr = spr; a.H = H; a.I = I;
     a.stream_rows = stream_rows_for(H, I);
+    a.tile_rows = tile_rows_for(H, I);
     a.ntw = I / 128;
     a.nts = I / 64;
-    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(max_tiles(cap, spr) * a.nts), dim3(kThreads), kLdsBytes, st, a);
+    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(max_tiles(cap, spr, a.tile_rows) * a.nts), dim3(kThreads), kLdsBytes, st, a);
     return launched();
 }
 
@@ -545,9 +555,10 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     a.group_offsets = group_offsets;
     a.T = T; a.k = k; a.spr = spr; a.H = H; a.I = I;
     a.stream_rows = stream_rows_for(H, I);
+    a.tile_rows = tile_rows_for(H, I);
     a.ntw = (H + 255) / 256;
     a.nts = H / 128;
-    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(max_tiles(cap, spr) * a.nts), dim3(kThreads), kLdsBytes, st, a);
+    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(max_tiles(cap, spr, a.tile_rows) * a.nts), dim3(kThreads), kLdsBytes, st, a);
     return launched();
 }
 
