@@ -87,6 +87,30 @@ class HotPath:
         api.moe_unpermute(self.y, self.pb["pair_row"], self.tw, out=self.out)
         m(5)
 
+    def graph_ms_per_step(self, g: int, replays: int = 20) -> float:
+        """The same step replayed from a HIP graph (one step per weight copy captured, so the rotation
+        is kept): what a serving loop that captures the layer would see; no events inside."""
+        torch = self.torch
+        n = len(self.copies[g])
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        self.step(g)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(n):
+                    self.step(g)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(replays):
+            graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / (n * replays)
+
     def ffn_only_us(self, g: int, iters: int = 3) -> float:
         torch = self.torch
         self.step(g)
@@ -129,12 +153,39 @@ class HotPath:
         return max(wall_ms, dev_ms) / steps, {n: stage[n] for n in self.STAGES}
 
 
+def graph_replay_us(torch, launch, reps: int = 20, replays: int = 10) -> float:
+    """Kernel-only latency of `launch()`: `reps` launches captured into one HIP graph (no memsets, no
+    events inside), mean over `replays` replays."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    launch()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(reps):
+                launch()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(replays):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    return 1e3 * a.elapsed_time(b) / (reps * replays)
+
+
 def routing_sweep(api, torch, W, quick: bool):
-    """Routing-only latency at the sweep shape (G=16, 58 layers per launch), us per batch."""
+    """Routing-only latency and max activated experts per rank at the sweep shape (G=16, 58 layers,
+    each with its own popularity permutation): T x Zipf s grid, METRO vs token-balanced.  Per cell:
+    us per batch with all 58 layers in one launch, us of a single-layer launch (events around 50
+    back-to-back launches), the same inside a HIP graph replay (kernel only), mean max-activated."""
     w = W.DSV3_SWEEP
     rows = []
-    for T in ((1024,) if quick else W.SWEEP_T):
-        s2e, ids = W.routing_inputs_layers(w, T=T, s=1.0)
+    cells = [(1024, 1.0)] if quick else [(T, s) for T in W.SWEEP_T for s in W.SWEEP_S]
+    for T, s in cells:
+        s2e, ids = W.routing_inputs_layers(w, T=T, s=s)
         d_ids, d_s2e = torch.from_numpy(ids).cuda(), torch.from_numpy(s2e).cuda()
         ref = {}
         for name, fn in (("metro", api.metro_route), ("token_balanced", api.metro_route_token_balanced)):
@@ -154,11 +205,34 @@ def routing_sweep(api, torch, W, quick: bool):
                 fn(d_ids[:1], d_s2e[:1], w.N, w.G, w.spr, out=one)
             c.record()
             torch.cuda.synchronize()
+            assert int(buf["err_flag"].abs().sum().item()) == 0
             ref[name] = dict(us_per_batch_58_layers_per_launch=round(1e3 * a.elapsed_time(b) / n / w.layers, 3),
                              us_per_single_layer_launch=round(1e3 * b.elapsed_time(c) / n, 3),
+                             us_single_layer_graph_replay=round(graph_replay_us(
+                                 torch, lambda: fn(d_ids[:1], d_s2e[:1], w.N, w.G, w.spr, out=one)), 3),
                              max_activated_per_rank_mean=round(float(buf["rank_active"].max(dim=1).values.float().mean()), 3))
-        rows.append(dict(T=T, s=1.0, **ref))
+        rows.append(dict(T=T, s=s, **ref))
     return rows
+
+
+def routing_quality(oracle, W, sweep_rows):
+    """Sec. 4.2's exact solver (binary search on lambda + bipartite matching, the oracle's CPU code) on the
+    same sweep cells: mean optimal lambda next to the measured METRO / token-balanced means, METRO's gap,
+    and the solver's CPU time per batch."""
+    w = W.DSV3_SWEEP
+    out = []
+    for row in sweep_rows:
+        s2e, ids = W.routing_inputs_layers(w, T=row["T"], s=row["s"])
+        cnts = [oracle.count(ids[l], w.N) for l in range(w.layers)]
+        t0 = time.perf_counter()
+        opt = [oracle.matching_opt(cnts[l], s2e[l], w.N, w.G, w.spr) for l in range(w.layers)]
+        us = 1e6 * (time.perf_counter() - t0) / w.layers
+        lam_opt, lam_me = float(np.mean(opt)), row["metro"]["max_activated_per_rank_mean"]
+        out.append(dict(T=row["T"], s=row["s"], lambda_opt_mean=round(lam_opt, 3), lambda_metro_mean=lam_me,
+                        lambda_token_balanced_mean=row["token_balanced"]["max_activated_per_rank_mean"],
+                        metro_gap_pct=round(100.0 * (lam_me / lam_opt - 1.0), 2),
+                        exact_solver_us_per_batch_cpu=round(us, 1)))
+    return out
 
 
 def cpu_baseline(oracle, W, w, ids, s2e, host_x, host_w13, host_w2, perm, ffn_bytes, budget_s: float):
@@ -252,12 +326,13 @@ def main() -> int:
         g = max(per_rank, key=per_rank.get)
         hp.copies = {g: hp.copies[g]}
         ms_per_step, stage = hp.timed(g, args.steps, args.warmup)
+        graph_ms = hp.graph_ms_per_step(g)
         assert int(hp.rb["err_flag"].item()) == 0
         active = int(hp.rb["rank_active"][0, g].item())
         P = int(hp.pb["n_pairs"].item())
         gu_b, dn_b = algorithmic_bytes(active, P, w.H, w.I)
         ffn_us = stage["gate_up"] + stage["down"]
-        result[routing] = dict(rank=g, ms_per_step=ms_per_step, stage_us={k: round(v, 2) for k, v in stage.items()},
+        result[routing] = dict(rank=g, ms_per_step=ms_per_step, graph_ms=graph_ms, stage_us={k: round(v, 2) for k, v in stage.items()},
                                ffn_us=ffn_us, active=active, pairs=P, bytes=(gu_b, dn_b),
                                lam=int(hp.rb["rank_active"].max().item()),
                                per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank.items()},
@@ -284,6 +359,7 @@ def main() -> int:
         "max_activated_per_rank": {"metro": me["lam"]},
         "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
         "stage_us": me["stage_us"],
+        "ms_per_step_hip_graph": {"metro": round(me["graph_ms"], 4)},
         "per_rank_ffn_us": {"metro": me["per_rank_ffn_us"]},
         "roofline": {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(gu_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
@@ -298,6 +374,7 @@ def main() -> int:
         line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
         line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
         line["ms_per_step_token_balanced"] = round(tb["ms_per_step"], 4)
+        line["ms_per_step_hip_graph"]["token_balanced"] = round(tb["graph_ms"], 4)
         line["routing_sweep"] = routing_sweep(api, torch, W, quick=False)
     if not args.no_cpu_baseline:
         from oracle import metro_oracle as oracle
@@ -309,6 +386,13 @@ def main() -> int:
         perm["n_pairs"] = int(perm["n_pairs"][0])
         line["cpu_baseline"] = cpu_baseline(oracle, W, w, ids, s2e, host(x), host(shares[g][0]), host(shares[g][1]),
                                             perm, gu_b + dn_b, args.cpu_budget)
+        cnt = oracle.count(ids, w.N)
+        t0 = time.perf_counter()
+        lam_opt = oracle.matching_opt(cnt, s2e, w.N, w.G, w.spr)
+        line["cpu_baseline"]["exact_solver"] = dict(lambda_opt=int(lam_opt), lambda_metro=me["lam"],
+                                                    us_per_batch_cpu=round(1e6 * (time.perf_counter() - t0), 1))
+        if "routing_sweep" in line:
+            line["cpu_baseline"]["routing_quality"] = routing_quality(oracle, W, line["routing_sweep"])
     print(json.dumps(line))
     return 0
 
