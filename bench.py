@@ -262,6 +262,48 @@ def cpu_baseline(oracle, W, w, ids, s2e, host_x, host_w13, host_w2, perm, ffn_by
                 ffn_us_extrapolated=round(1e6 * full_s, 1), route_us_per_batch=round(route_us, 2))
 
 
+def replication_sweep(api, torch, W, steps: int, warmup: int):
+    """The paper's main axis (Sec. 6.2, Fig. 10): replication ratio 1.0x .. 1.5x at the three FFN
+    shapes, at the config's batch and at the 32-tokens-per-rank decode batch.  Per cell and router:
+    max activated experts per rank, pairs on the slowest rank, its FFN time (gate/up + down events)."""
+    rows = []
+    for base in (W.QWEN3_30B, W.QWEN3_235B, W.DSV3):
+        lw13, lw2 = W.device_expert_weights(base, "cuda")
+        for ratio in (1.0, 1.125, 1.25, 1.5):
+            spr = int(round(base.N * ratio / base.G))
+            for T in sorted({32 * base.G, base.T}):
+                w = base.with_(spr=spr, T=T)
+                _, s2e, ids = W.routing_inputs(w)
+                d_ids = torch.from_numpy(ids).cuda().unsqueeze(0)
+                d_s2e = torch.from_numpy(s2e).cuda().unsqueeze(0)
+                x = W.device_activations(w, "cuda")
+                tw = torch.from_numpy(W.gating_weights(w.T, w.k, w.seed(0, 4))).cuda()
+                shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr, pad=True),
+                              W.device_rank_share(lw2, s2e, g, w.spr, pad=True)) for g in range(w.G)}
+                cell = dict(workload=base.name, replication=ratio, slots_per_rank=spr, T=T)
+                for routing in ("metro", "token_balanced"):
+                    hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
+                    per_rank = {g: hp.ffn_only_us(g) for g in range(w.G)}
+                    g = max(per_rank, key=per_rank.get)
+                    hp.copies = {g: hp.copies[g]}
+                    _, stage = hp.timed(g, steps, warmup)
+                    assert int(hp.rb["err_flag"].item()) == 0
+                    cell[routing] = dict(max_activated=int(hp.rb["rank_active"].max().item()), slowest_rank=g,
+                                         activated=int(hp.rb["rank_active"][0, g].item()),
+                                         pairs=int(hp.pb["n_pairs"].item()),
+                                         ffn_us=round(stage["gate_up"] + stage["down"], 1))
+                    del hp
+                cell["ffn_time_metro_over_token_balanced"] = round(
+                    cell["metro"]["ffn_us"] / cell["token_balanced"]["ffn_us"], 3)
+                rows.append(cell)
+                print(json.dumps(cell), file=sys.stderr, flush=True)
+                del shares, x
+                torch.cuda.empty_cache()
+        del lw13, lw2
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -277,6 +319,9 @@ def main() -> int:
                          "elements, the layout the library recommends)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for rocprofv3 byte counters)")
+    ap.add_argument("--replication-sweep", action="store_true",
+                    help="instead of the benchmark line: METRO vs token-balanced over replication ratios "
+                         "1.0x..1.5x at the three FFN shapes (one JSON line of its own)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the G expert-parallel ranks are logical); "
@@ -293,6 +338,10 @@ def main() -> int:
         return 2
     api.load()
     torch.cuda.set_device(0)
+    if args.replication_sweep:
+        print(json.dumps({"mode": "replication_sweep", "unit": "us (slowest-rank expert FFN)", "steps": args.steps,
+                          "rows": replication_sweep(api, torch, W, args.steps, args.warmup)}))
+        return 0
     w = W.WORKLOADS[args.workload]
     if w.H == 0:
         print("that workload has no FFN shape", file=sys.stderr)
