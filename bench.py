@@ -319,6 +319,7 @@ def main() -> int:
                          "elements, the layout the library recommends)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for rocprofv3 byte counters)")
+    ap.add_argument("--no-hip-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--replication-sweep", action="store_true",
                     help="instead of the benchmark line: METRO vs token-balanced over replication ratios "
                          "1.0x..1.5x at the three FFN shapes (one JSON line of its own)")
@@ -375,7 +376,7 @@ def main() -> int:
         g = max(per_rank, key=per_rank.get)
         hp.copies = {g: hp.copies[g]}
         ms_per_step, stage = hp.timed(g, args.steps, args.warmup)
-        graph_ms = hp.graph_ms_per_step(g)
+        graph_ms = float("nan") if args.no_hip_graph else hp.graph_ms_per_step(g)
         assert int(hp.rb["err_flag"].item()) == 0
         active = int(hp.rb["rank_active"][0, g].item())
         P = int(hp.pb["n_pairs"].item())
@@ -408,7 +409,7 @@ def main() -> int:
         "max_activated_per_rank": {"metro": me["lam"]},
         "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
         "stage_us": me["stage_us"],
-        "ms_per_step_hip_graph": {"metro": round(me["graph_ms"], 4)},
+        "ms_per_step_hip_graph": {"metro": None if args.no_hip_graph else round(me["graph_ms"], 4)},
         "per_rank_ffn_us": {"metro": me["per_rank_ffn_us"]},
         "roofline": {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(gu_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
@@ -423,7 +424,7 @@ def main() -> int:
         line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
         line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
         line["ms_per_step_token_balanced"] = round(tb["ms_per_step"], 4)
-        line["ms_per_step_hip_graph"]["token_balanced"] = round(tb["graph_ms"], 4)
+        line["ms_per_step_hip_graph"]["token_balanced"] = None if args.no_hip_graph else round(tb["graph_ms"], 4)
         line["routing_sweep"] = routing_sweep(api, torch, W, quick=False)
     if not args.no_cpu_baseline:
         from oracle import metro_oracle as oracle

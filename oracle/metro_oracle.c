@@ -18,6 +18,11 @@
  *   - oracle_permute                pinned against a library stable sort.
  *   - oracle_ffn / oracle_unpermute pinned against library matmuls in float64 and
  *                                   hand-computable special cases.
+ *   - oracle_gate_topk              router logits + top-k (the step before the routing solve,
+ *                                   Sec. 4.3); pinned against a library matmul + argsort +
+ *                                   softmax, one-hot closed forms, ties and brute force.  The
+ *                                   paper does not define the gate itself: the reading is the
+ *                                   common softmax-over-the-selected-logits router.
  */
 #include <math.h>
 #include <stdint.h>
@@ -326,6 +331,49 @@ int oracle_unpermute(const double* y_perm, const int32_t* pair_row, const float*
             for (int c = 0; c < H; ++c)
                 out[(int64_t)t * H + c] += (double)topk_w[(int64_t)t * k + j] * y_perm[(int64_t)r * H + c];
         }
+    }
+    return ORACLE_OK;
+}
+
+/* Router gate + top-k on the full (gathered) token set, Sec. 4.3: the step that produces the
+ * global top-k ids the routing solve consumes.  The paper leaves the gate to the model; reading:
+ *     logit[t][e] = sum_h x[t][h] * w_gate[e][h]
+ *     ids[t][0..k) = the k experts with the largest logits, in descending logit order, equal
+ *                    logits in ascending expert id
+ *     w[t][j]      = exp(logit[t][ids[t][j]]) / sum_j' exp(logit[t][ids[t][j']])
+ * (softmax over all experts, top-k, renormalise -- the same numbers).  Everything in double.
+ * logits_out[T,N] and cnt[N] (T[i] of Sec. 4.1) may be NULL. */
+int oracle_gate_topk(const void* x, const void* w_gate, int dtype, int T, int H, int N, int k,
+                     int32_t* ids, double* w, double* logits_out, int32_t* cnt) {
+    if (T < 0 || H < 1 || N < 1 || k < 1 || k > N) return ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        double* logit = (double*)malloc(sizeof(double) * N);
+        char* taken = (char*)malloc(N);
+        for (int e = 0; e < N; ++e) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                acc += load_elem(x, dtype, (int64_t)t * H + h) * load_elem(w_gate, dtype, (int64_t)e * H + h);
+            logit[e] = acc;
+            taken[e] = 0;
+            if (logits_out) logits_out[(int64_t)t * N + e] = acc;
+        }
+        for (int j = 0; j < k; ++j) {              /* selection: largest remaining, lowest id first */
+            int best = -1;
+            for (int e = 0; e < N; ++e)
+                if (!taken[e] && (best < 0 || logit[e] > logit[best])) best = e;
+            taken[best] = 1;
+            ids[(int64_t)t * k + j] = best;
+        }
+        double top = logit[ids[(int64_t)t * k]], sum = 0.0;
+        for (int j = 0; j < k; ++j) sum += exp(logit[ids[(int64_t)t * k + j]] - top);
+        for (int j = 0; j < k; ++j) w[(int64_t)t * k + j] = exp(logit[ids[(int64_t)t * k + j]] - top) / sum;
+        free(logit);
+        free(taken);
+    }
+    if (cnt) {                                     /* T[i]: pairs that selected expert i */
+        for (int e = 0; e < N; ++e) cnt[e] = 0;
+        for (int64_t p = 0; p < (int64_t)T * k; ++p) cnt[ids[p]] += 1;
     }
     return ORACLE_OK;
 }

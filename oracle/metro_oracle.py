@@ -168,3 +168,24 @@ def unpermute(y_perm: np.ndarray, pair_row: np.ndarray, topk_w: np.ndarray) -> n
     out = np.empty((T, H), np.float64)
     _check(_load().oracle_unpermute(_p(y), _p(pr), _p(w), T, k, H, _p(out)))
     return out
+
+
+def gate_topk(x: np.ndarray, w_gate: np.ndarray, k: int, want_logits: bool = False) -> dict:
+    """x[T,H], w_gate[N,H] (float32, or uint16 bfloat16 bits) -> ids[T,k] int32 (descending logit, ties
+    to the lower id), w[T,k] float64 (softmax over the selected logits), cnt[N] int32 (pairs per expert);
+    logits[T,N] float64 when want_logits."""
+    x = np.ascontiguousarray(x)
+    w_gate = np.ascontiguousarray(w_gate)
+    code = _dtype_code(x)
+    assert _dtype_code(w_gate) == code and x.shape[1] == w_gate.shape[1]
+    T, H = x.shape
+    N = w_gate.shape[0]
+    ids = np.empty((T, k), np.int32)
+    w = np.empty((T, k), np.float64)
+    cnt = np.empty(N, np.int32)
+    logits = np.empty((T, N), np.float64) if want_logits else None
+    _check(_load().oracle_gate_topk(_p(x), _p(w_gate), code, T, H, N, k, _p(ids), _p(w), _p(logits), _p(cnt)))
+    out = dict(ids=ids, w=w, cnt=cnt)
+    if want_logits:
+        out["logits"] = logits
+    return out

@@ -209,6 +209,13 @@ def expert_weights(N: int, H: int, I: int, seed: int, dtype: str) -> Tuple[np.nd
     return f32_to_bf16_bits(w13), f32_to_bf16_bits(w2)
 
 
+def gate_weights(N: int, H: int, seed: int, dtype: str) -> np.ndarray:
+    """Router weights w_gate[N,H] ~ N(0, 1/H), so that logits of N(0,1) activations are ~ N(0,1);
+    float32 for "f32", uint16 bfloat16 bit patterns for "bf16"."""
+    wg = (_rng(seed).standard_normal((N, H)) / np.sqrt(H)).astype(np.float32)
+    return wg if dtype == "f32" else f32_to_bf16_bits(wg)
+
+
 def rank_share(w: np.ndarray, slot_to_expert: np.ndarray, g: int, spr: int) -> np.ndarray:
     """Weights of the spr slots of rank g, [spr, ...]; an empty slot (-1) holds zeros."""
     ex = slot_to_expert[g * spr:(g + 1) * spr]
