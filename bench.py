@@ -215,6 +215,29 @@ def routing_sweep(api, torch, W, quick: bool):
     return rows
 
 
+def gate_topk_timing(api, torch, W, w, x):
+    """Router gate + top-k at the workload's shape (the step before the path; not part of a step)."""
+    wg = torch.from_numpy(W.gate_weights(w.N, w.H, w.seed(0, 5), "bf16")).view(torch.bfloat16).cuda()
+    out = api.moe_gate_topk(x, wg, w.k)
+    ws = torch.empty((api.load().moe_gate_topk_workspace_bytes(w.T, w.H, w.N, api.DTYPE_BF16),), dtype=torch.uint8,
+                     device="cuda")
+    run = lambda: api.moe_gate_topk(x, wg, w.k, out=out, ws=ws)
+    for _ in range(5):
+        run()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = 50
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(n):
+        run()
+    b.record()
+    torch.cuda.synchronize()
+    flop = 2.0 * w.T * w.H * w.N
+    us = 1e3 * a.elapsed_time(b) / n
+    return dict(us_per_call=round(us, 2), us_graph_replay=round(graph_replay_us(torch, run), 2),
+                tflops=round(flop / us / 1e6, 1), operand_mb=round((w.T + w.N) * w.H * 2 / 1e6, 1))
+
+
 def routing_quality(oracle, W, sweep_rows):
     """Sec. 4.2's exact solver (binary search on lambda + bipartite matching, the oracle's CPU code) on the
     same sweep cells: mean optimal lambda next to the measured METRO / token-balanced means, METRO's gap,
@@ -417,6 +440,7 @@ def main() -> int:
                      "down_kernel": {"achieved": round(dn_b / (me["stage_us"]["down"] * 1e-6) / 1e9, 1),
                                      "algorithmic_bytes_per_launch": dn_b}},
     }
+    line["gate_topk"] = gate_topk_timing(api, torch, W, w, x)
     if "token_balanced" in result:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)

@@ -94,6 +94,33 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
                 int32_t* perm_pair, int32_t* pair_row, int32_t* n_pairs, void* stream);
 
 /*
+ * moe_gate_topk -- router gate and top-k over the full (gathered) token set: the step that builds
+ * the global top-k knowledge the routing solve consumes (Sec. 4.3: tokens are all-gathered and every
+ * rank runs top-k on all of them).  The paper leaves the gate itself to the model; this is the
+ * common softmax router:
+ *     logit[t][e]  = x[t] . w_gate[e]
+ *     topk_ids[t]  = the k experts with the largest logits, descending; equal logits: lower id first
+ *     topk_w[t][j] = exp(logit[t][ids[t][j]]) / sum over the k selected of exp(logit)
+ *     expert_count[e] = number of (token, expert) pairs that selected e      (T[i] of Sec. 4.1)
+ *
+ *   x        [T,H]   dtype     activations (rows H elements apart)
+ *   w_gate   [N,H]   dtype     router weights, rows ldw >= H elements apart
+ *   topk_ids [T,k]   int32     out; valid input for metro_route / metro_route_token_balanced
+ *   topk_w   [T,k]   float32   out; valid input for moe_unpermute
+ *   expert_count [N] int32     out, may be NULL
+ *   ws                         workspace of moe_gate_topk_workspace_bytes(); 256-byte aligned
+ *   dtype  METRO_DTYPE_BF16: bf16 operands, fp32 accumulation on the matrix cores when H % 32 == 0,
+ *          N % 64 == 0, ldw % 8 == 0 and x, w_gate are 16-byte aligned; other shapes and
+ *          METRO_DTYPE_F32 take a plain fp32 kernel.  Logits are summed in a fixed order, so the
+ *          result is deterministic; NaN logits sort below every number.
+ * Limits: N <= 512, k <= min(N, 64), T*k < 2^24.  T == 0 is a no-op.
+ */
+size_t moe_gate_topk_workspace_bytes(int T, int H, int N, int dtype);
+int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, int H, int N, int k, int dtype,
+                  int32_t* topk_ids, float* topk_w, int32_t* expert_count, void* ws, size_t ws_bytes,
+                  void* stream);
+
+/*
  * moe_grouped_ffn -- SwiGLU expert FFN over the token lists of one rank.  Only slots with at
  * least one row are touched, so HBM weight traffic scales with the number of activated
  * experts (Sec. 3.2).  For row r of local slot l, token t = perm_pair[r] / k:

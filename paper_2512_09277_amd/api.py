@@ -22,7 +22,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ("metro_status_string", "metro_route", "metro_route_token_balanced", "moe_permute",
            "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gate_up",
-           "moe_grouped_ffn_down", "moe_unpermute")
+           "moe_grouped_ffn_down", "moe_unpermute", "moe_gate_topk_workspace_bytes", "moe_gate_topk")
 
 
 class MetroError(RuntimeError):
@@ -58,6 +58,10 @@ def load() -> ctypes.CDLL:
         lib.moe_grouped_ffn_down.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, sz, vp]
         lib.moe_unpermute.restype = ci
         lib.moe_unpermute.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        lib.moe_gate_topk_workspace_bytes.restype = sz
+        lib.moe_gate_topk_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        lib.moe_gate_topk.restype = ci
+        lib.moe_gate_topk.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -228,4 +232,30 @@ def moe_unpermute(y_perm: torch.Tensor, pair_row: torch.Tensor, topk_w: torch.Te
     _check(load().moe_unpermute(_dev(y_perm, y_perm.dtype, "y_perm"), _dev(pair_row, torch.int32, "pair_row"),
                                 _dev(topk_w, torch.float32, "topk_w"), T, k, H, code,
                                 _dev(out, y_perm.dtype, "out"), _stream()))
+    return out
+
+
+def moe_gate_topk(x: torch.Tensor, w_gate: torch.Tensor, k: int, out: Optional[dict] = None,
+                  ws: Optional[torch.Tensor] = None) -> dict:
+    """x [T,H], w_gate [N,H] (bf16 or f32; rows may be strided) -> dict(topk_ids [T,k] int32,
+    topk_w [T,k] float32, expert_count [N] int32)."""
+    T, H = x.shape
+    N = w_gate.shape[0]
+    if w_gate.shape[1] != H or w_gate.stride(1) != 1:
+        raise ValueError("w_gate must be [N,H] with contiguous rows")
+    code = _dtype_code(x)
+    if out is None:
+        out = dict(topk_ids=torch.empty((T, k), dtype=torch.int32, device=x.device),
+                   topk_w=torch.empty((T, k), dtype=torch.float32, device=x.device),
+                   expert_count=torch.empty((N,), dtype=torch.int32, device=x.device))
+    if ws is None:
+        ws = torch.empty((int(load().moe_gate_topk_workspace_bytes(T, H, N, code)),), dtype=torch.uint8,
+                         device=x.device)
+    if not (w_gate.is_cuda and w_gate.dtype == x.dtype):
+        raise TypeError(f"w_gate: expected a {x.dtype} device tensor")
+    ldw = w_gate.stride(0) if N > 1 else H
+    _check(load().moe_gate_topk(_dev(x, x.dtype, "x"), w_gate.data_ptr(), ldw, T, H, N, k, code, _dev(out["topk_ids"], torch.int32, "topk_ids"),
+                                _dev(out["topk_w"], torch.float32, "topk_w"),
+                                _dev(out["expert_count"], torch.int32, "expert_count"),
+                                _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
     return out

@@ -1,0 +1,338 @@
+// moe_gate_topk for gfx950: router logits + top-k + gating weights on the full (gathered) token set,
+// the step that produces the global top-k ids the routing solve consumes (Sec. 4.3 of arxiv
+// 2512.09277: every rank runs top-k over all tokens).
+//
+//   logit[t][e] = x[t] . w_gate[e]        ids[t] = k largest logits (descending, ties to the lower id)
+//   w[t][j]     = softmax over the k selected logits          cnt[e] = pairs that selected expert e
+//
+// The logits are a small dense contraction ([T,H] x [H,N], 3.8 GFLOP at T=1024, H=7168, N=256) whose
+// operands total 18 MB: neither the matrix cores nor HBM is the limit, launch latency and the number
+// of busy CUs are.  Launches:
+//   1. gate_logits_mfma_kernel: 64 tokens x 64 experts x one K chunk per workgroup (split-K so that
+//      ~512 workgroups exist at any batch size); both operands go straight from global memory into
+//      the MFMA operand layout; fp32 partial sums land in the workspace, part[chunk][t][e];
+//   2. gate_topk_kernel: one wave per token sums the chunks in a fixed order (deterministic), picks the
+//      top-k by k rounds of a wave-wide arg-max over (logit, -id) and forms the softmax weights;
+//   3. (only when the caller wants expert_count) gate_count_kernel: pairs per expert, one workgroup.
+// Shapes the MFMA kernel does not take (fp32, N not a multiple of 64, H not a multiple of 32) use a
+// plain one-wave-per-logit kernel in fp32.
+#include <hip/hip_runtime.h>
+#include <float.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "device_utils.h"
+#include "metro.h"
+
+namespace metro {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kMaxN = 512;
+constexpr int kTokTile = 16;              // tokens of one matrix-instruction sub-tile
+constexpr int kMinChunkSteps = 2;           // K steps of 32 a wave gets at least
+
+struct GateArgs {
+    const void* x;
+    const void* w_gate;
+    float* part;              // [n_chunks][T][N]
+    int T, H, N, ldw;
+    int steps_per_chunk;      // K steps of 32 per chunk
+};
+
+// One workgroup: 16*MT tokens x 64 experts x one K chunk; its four waves split the chunk's K steps and
+// meet through LDS, so one partial tile leaves the workgroup.  (Splitting K over workgroups only would
+// need four times the chunks for the same number of waves, and the partial sums -- written here, read
+// by the top-k kernel -- would outweigh the operands.)
+// Lane (r16, q) supplies the 8 elements k = kk + q*8 .. +8 of expert row r16 of a block (A operand) and of
+// token row r16 of a sub-tile (B operand); D[i][j]: i = expert 4*q + v of the block, j = token r16.
+constexpr int kExpTile = 64, kNB = kExpTile / 16;
+
+template <int MT>
+__global__ __launch_bounds__(kThreads, 2) void gate_logits_mfma_kernel(GateArgs a) {
+    __shared__ floatx4 xch[3][kNB * MT][kWave];                   // sums of waves 1..3
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int r16 = lane & 15, q = lane >> 4;
+    // K chunk fastest in launch order: workgroup i runs on XCD i mod 8, so with a multiple of 8 chunks
+    // every XCD (own L2) streams its own K range of x and w_gate instead of all eight fetching everything.
+    const int chunk = blockIdx.x, t0 = blockIdx.y * (16 * MT), e0 = blockIdx.z * kExpTile;
+    const int n_steps = a.H / 32;
+    const int c_begin = chunk * a.steps_per_chunk, c_end = min(c_begin + a.steps_per_chunk, n_steps);
+    const int per_wave = (c_end - c_begin + 3) / 4;
+    const int s_begin = min(c_begin + wv * per_wave, c_end), s_end = min(s_begin + per_wave, c_end);
+    const char* xp[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int tok = min(t0 + mt * 16 + r16, a.T - 1);         // rows past the batch repeat the last token
+        xp[mt] = reinterpret_cast<const char*>(a.x) + ((size_t)tok * a.H + q * 8) * 2;
+    }
+    const char* wp = reinterpret_cast<const char*>(a.w_gate) + ((size_t)(e0 + r16) * a.ldw + q * 8) * 2;
+    const size_t blk = (size_t)16 * a.ldw * 2;                    // bytes between 16-row blocks
+
+    floatx4 acc[kNB][MT];
+#pragma unroll
+    for (int b = 0; b < kNB; ++b)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[b][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // U steps at a time: all their loads are issued before the first matrix instruction (the scheduling
+    // barrier keeps the compiler from sinking each load next to its use, which would leave one or two
+    // loads in flight per wave).
+    auto steps = [&](auto U, int s) {
+        constexpr int n = decltype(U)::value;
+        bf16x8 xb[n][MT], wa[n][kNB];
+#pragma unroll
+        for (int u = 0; u < n; ++u) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xb[u][mt] = *reinterpret_cast<const bf16x8*>(xp[mt] + (size_t)(s + u) * 64);
+#pragma unroll
+            for (int b = 0; b < kNB; ++b) wa[u][b] = *reinterpret_cast<const bf16x8*>(wp + b * blk + (size_t)(s + u) * 64);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < n; ++u)
+#pragma unroll
+            for (int b = 0; b < kNB; ++b)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[b][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[u][b], xb[u][mt], acc[b][mt], 0, 0, 0);
+    };
+    int s = s_begin;
+    for (; s + 3 <= s_end; s += 3) steps(std::integral_constant<int, 3>{}, s);
+    for (; s < s_end; ++s) steps(std::integral_constant<int, 1>{}, s);
+
+    if (wv > 0) {
+#pragma unroll
+        for (int b = 0; b < kNB; ++b)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xch[wv - 1][b * MT + mt][lane] = acc[b][mt];
+    }
+    __syncthreads();
+    if (wv == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int t = t0 + mt * 16 + r16;
+            float* out = a.part + ((size_t)chunk * a.T + min(t, a.T - 1)) * a.N + e0 + q * 4;
+#pragma unroll
+            for (int b = 0; b < kNB; ++b) {
+                floatx4 sum = acc[b][mt];
+#pragma unroll
+                for (int o = 0; o < 3; ++o) sum += xch[o][b * MT + mt][lane];     // waves in a fixed order
+                if (t < a.T) *reinterpret_cast<floatx4*>(out + b * 16) = sum;
+            }
+        }
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ float elem_f32(const void* p, size_t i);
+template <>
+__device__ __forceinline__ float elem_f32<float>(const void* p, size_t i) { return ((const float*)p)[i]; }
+template <>
+__device__ __forceinline__ float elem_f32<__bf16>(const void* p, size_t i) { return (float)((const __bf16*)p)[i]; }
+
+// Any shape, fp32 arithmetic: one wave per logit, a single chunk.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gate_logits_general_kernel(GateArgs a) {
+    const int t = blockIdx.x;
+    const int e = blockIdx.y * (kThreads / kWave) + wave_id();
+    if (e >= a.N) return;
+    float acc = 0.f;
+    for (int h = lane_id(); h < a.H; h += kWave)
+        acc = fmaf(elem_f32<T>(a.x, (size_t)t * a.H + h), elem_f32<T>(a.w_gate, (size_t)e * a.ldw + h), acc);
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) acc += __shfl_xor(acc, d);
+    if (lane_id() == 0) a.part[(size_t)t * a.N + e] = acc;
+}
+
+struct Cand {
+    float v;
+    int id;
+};
+__device__ __forceinline__ bool better(const Cand& a, const Cand& b) { return a.v > b.v || (a.v == b.v && a.id < b.id); }
+
+// One wave per token.  Lane l holds the logits of experts l, l + 64, ... (kPerLane = ceil(N / 64) of them).
+template <int kPerLane>
+__global__ __launch_bounds__(kThreads) void gate_topk_kernel(const float* __restrict__ part, int n_chunks, int T, int N,
+                                                              int k, int32_t* __restrict__ ids, float* __restrict__ w) {
+    const int t = blockIdx.x * (kThreads / kWave) + wave_id();
+    if (t >= T) return;                                          // uniform per wave
+    const int l = lane_id();
+    // Chunk sums in ascending chunk order (fixed, so the result is deterministic); the loads of a batch
+    // of chunks x all of the lane's experts are issued together, only the additions are sequential.
+    float v[kPerLane];
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) v[j] = 0.f;
+    const float* row = part + (size_t)t * N + l;
+    const size_t chunk_stride = (size_t)T * N;
+    constexpr int kBatch = kPerLane <= 4 ? 8 : 4;
+    for (int c0 = 0; c0 < n_chunks; c0 += kBatch) {
+        float p[kBatch][kPerLane];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int c = min(c0 + u, n_chunks - 1);             // past the end: re-read, not added
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j)
+                p[u][j] = (j * kWave + l < N) ? row[c * chunk_stride + j * kWave] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (c0 + u < n_chunks) {
+#pragma unroll
+                for (int j = 0; j < kPerLane; ++j) v[j] += p[u][j];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        if (v[j] != v[j]) v[j] = -FLT_MAX;                       // NaN sorts below every number
+        if (j * kWave + l >= N) v[j] = -INFINITY;                // experts past N never win
+    }
+    uint32_t taken = 0;                                          // bit j: v[j] already selected
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j)
+        if (j * kWave + l >= N) taken |= 1u << j;
+    float my_v = 0.f;
+    int my_id = 0;
+    for (int r = 0; r < k; ++r) {
+        Cand best{-INFINITY, 0x7fffffff};
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const Cand c{v[j], j * kWave + l};
+            if (!((taken >> j) & 1u) && better(c, best)) best = c;
+        }
+#pragma unroll
+        for (int d = kWave / 2; d > 0; d >>= 1) {
+            const Cand o{__shfl_xor(best.v, d), __shfl_xor(best.id, d)};
+            if (better(o, best)) best = o;
+        }
+        if ((best.id & (kWave - 1)) == l) taken |= 1u << (best.id >> 6);   // k <= N: a real expert
+        if (l == r) {
+            my_v = best.v;
+            my_id = best.id;
+        }
+    }
+    // lanes 0..k-1 hold the selection in descending order; softmax over it
+    const float top = __shfl(my_v, 0);
+    const float ex = l < k ? expf(my_v - top) : 0.f;
+    float sum = ex;
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) sum += __shfl_xor(sum, d);
+    if (l < k) {
+        ids[(size_t)t * k + l] = my_id;
+        w[(size_t)t * k + l] = ex / sum;
+    }
+}
+
+// T[i] of Sec. 4.1: pairs per expert, one workgroup, LDS histogram.  (Device-scope atomics from every
+// token's wave onto the same few cache lines serialise across the eight L2s: measured ~10 us at
+// T = 1024, more than the rest of the top-k kernel.)
+constexpr int kCountThreads = 1024;
+__global__ __launch_bounds__(kCountThreads) void gate_count_kernel(const int32_t* __restrict__ ids, int n_pairs, int N,
+                                                                   int32_t* __restrict__ cnt) {
+    __shared__ int hist[kMaxN];
+    for (int e = threadIdx.x; e < N; e += kCountThreads) hist[e] = 0;
+    __syncthreads();
+    for (int p = threadIdx.x; p < n_pairs; p += kCountThreads) {
+        const int e = ids[p];
+        if (e >= 0 && e < N) atomicAdd(&hist[e], 1);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < N; e += kCountThreads) cnt[e] = hist[e];
+}
+
+inline bool gate_mfma_shape(int H, int N, int dtype) {
+    return dtype == METRO_DTYPE_BF16 && H % 32 == 0 && N % kExpTile == 0 && N <= kMaxN;
+}
+
+// Tokens per workgroup: 64 (four sub-tiles) unless the batch is a single sub-tile.
+inline int gate_tok_tile(int T) { return T > kTokTile ? 4 * kTokTile : kTokTile; }
+
+// K chunks: enough workgroups for two per CU (~512), each chunk at least kMinChunkSteps steps per wave.
+inline int gate_steps_per_chunk(int T, int H, int N) {
+    const int n_steps = H / 32, tile = gate_tok_tile(T);
+    const int tiles = ((T + tile - 1) / tile) * (N / kExpTile);
+    int chunks = (512 + tiles - 1) / tiles;
+    const int max_chunks = n_steps / (4 * kMinChunkSteps) > 0 ? n_steps / (4 * kMinChunkSteps) : 1;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks >= 8) chunks = chunks / 8 * 8;                      // one K range (or two, ...) per XCD
+    if (chunks < 1) chunks = 1;
+    return (n_steps + chunks - 1) / chunks;
+}
+inline int gate_chunks(int T, int H, int N, int dtype) {
+    if (!gate_mfma_shape(H, N, dtype)) return 1;
+    const int spc = gate_steps_per_chunk(T, H, N);
+    return (H / 32 + spc - 1) / spc;
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+}  // namespace metro
+
+extern "C" size_t moe_gate_topk_workspace_bytes(int T, int H, int N, int dtype) {
+    using namespace metro;
+    if (T < 0 || H < 1 || N < 1) return 0;
+    return align256((size_t)gate_chunks(T, H, N, dtype) * T * N * sizeof(float)) + 256;
+}
+
+extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, int H, int N, int k, int dtype,
+                             int32_t* topk_ids, float* topk_w, int32_t* expert_count, void* ws, size_t ws_bytes,
+                             void* stream) {
+    using namespace metro;
+    if (T < 0 || H < 1 || N < 1 || k < 1 || k > N) return METRO_ERR_INVALID_ARG;
+    if (dtype != METRO_DTYPE_BF16 && dtype != METRO_DTYPE_F32) return METRO_ERR_UNSUPPORTED;
+    if (N > kMaxN || k > kWave || (int64_t)T * k >= (1 << 24)) return METRO_ERR_UNSUPPORTED;
+    if (ldw < H) return METRO_ERR_INVALID_ARG;
+    if (T == 0) return METRO_OK;
+    if (!x || !w_gate || !topk_ids || !topk_w || !ws) return METRO_ERR_INVALID_ARG;
+    if (((uintptr_t)ws & 255) != 0) return METRO_ERR_INVALID_ARG;
+    if (ws_bytes < moe_gate_topk_workspace_bytes(T, H, N, dtype)) return METRO_ERR_WORKSPACE;
+    const bool mfma = gate_mfma_shape(H, N, dtype) && ldw % 8 == 0 &&
+                      (((uintptr_t)x | (uintptr_t)w_gate) & 15) == 0;
+    hipStream_t st = (hipStream_t)stream;
+    GateArgs a;
+    a.x = x;
+    a.w_gate = w_gate;
+    a.part = (float*)ws;
+    a.T = T; a.H = H; a.N = N; a.ldw = ldw;
+    int n_chunks = 1;
+    if (mfma) {
+        a.steps_per_chunk = gate_steps_per_chunk(T, H, N);
+        n_chunks = (H / 32 + a.steps_per_chunk - 1) / a.steps_per_chunk;
+        const int tile = gate_tok_tile(T);
+        const dim3 grid(n_chunks, (T + tile - 1) / tile, N / kExpTile);
+        if (tile == kTokTile)
+            hipLaunchKernelGGL(gate_logits_mfma_kernel<1>, grid, dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL(gate_logits_mfma_kernel<4>, grid, dim3(kThreads), 0, st, a);
+    }
+    if (!mfma) {
+        a.steps_per_chunk = 0;
+        n_chunks = 1;
+        const dim3 grid(T, (N + kThreads / kWave - 1) / (kThreads / kWave));
+        if (dtype == METRO_DTYPE_F32)
+            hipLaunchKernelGGL(gate_logits_general_kernel<float>, grid, dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL(gate_logits_general_kernel<__bf16>, grid, dim3(kThreads), 0, st, a);
+    }
+    if (hipGetLastError() != hipSuccess) return METRO_ERR_HIP;
+    const int per = kThreads / kWave;
+    const dim3 tgrid((T + per - 1) / per);
+    const float* part = (const float*)ws;
+    if (N <= 64)
+        hipLaunchKernelGGL(gate_topk_kernel<1>, tgrid, dim3(kThreads), 0, st, part, n_chunks, T, N, k, topk_ids, topk_w);
+    else if (N <= 128)
+        hipLaunchKernelGGL(gate_topk_kernel<2>, tgrid, dim3(kThreads), 0, st, part, n_chunks, T, N, k, topk_ids, topk_w);
+    else if (N <= 256)
+        hipLaunchKernelGGL(gate_topk_kernel<4>, tgrid, dim3(kThreads), 0, st, part, n_chunks, T, N, k, topk_ids, topk_w);
+    else
+        hipLaunchKernelGGL(gate_topk_kernel<8>, tgrid, dim3(kThreads), 0, st, part, n_chunks, T, N, k, topk_ids, topk_w);
+    if (expert_count)
+        hipLaunchKernelGGL(gate_count_kernel, dim3(1), dim3(kCountThreads), 0, st, (const int32_t*)topk_ids, T * k, N,
+                           expert_count);
+    return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
+}
