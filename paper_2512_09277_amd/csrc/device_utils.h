@@ -11,25 +11,18 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 __device__ __forceinline__ uint64_t lanes_below() { return (1ull << lane_id()) - 1ull; }
 
-// For the lanes with `valid`, the number of lower lanes holding the same key; `total`
-// receives the number of lanes holding it.  One ballot per distinct key in the wave.
-__device__ __forceinline__ int wave_rank_by_key(int key, bool valid, int& total) {
-    uint64_t todo = __ballot(valid);
-    int rank = 0;
-    total = 0;
-    const uint64_t below = lanes_below();
-    while (todo) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const int leader_key = __builtin_amdgcn_readlane(key, leader);
-        const bool mine = valid && key == leader_key;
-        const uint64_t same = __ballot(mine);
-        if (mine) {
-            rank = __popcll(same & below);
-            total = __popcll(same);
-        }
-        todo &= ~same;
+// For the lanes with `valid`, the number of lower lanes holding the same key; `total` receives the
+// number of lanes holding it.  Keys are < 2^bits.  One ballot per key bit: the lanes that agree with
+// mine on every bit are the lanes with my key (no loop over the distinct keys of the wave).
+__device__ __forceinline__ int wave_rank_by_key(int key, bool valid, int bits, int& total) {
+    uint64_t same = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+        const bool mine = (key >> b) & 1;
+        const uint64_t set = __ballot(mine);
+        same &= mine ? set : ~set;
     }
-    return rank;
+    total = __popcll(same);
+    return __popcll(same & lanes_below());
 }
 
 // Stable occurrence numbering of n items by key, in item order, by one workgroup.
@@ -37,13 +30,14 @@ __device__ __forceinline__ int wave_rank_by_key(int key, bool valid, int& total)
 // After pass 1 + prefix, hist[w][key] = items with that key owned by lower waves, tot[key] = all.
 // Each wave owns a contiguous run of 64-item chunks, so item order = (wave, chunk, lane).
 struct OrderedCounter {
-    int n, n_keys, chunks_per_wave;
+    int n, n_keys, key_bits, chunks_per_wave;
     int* hist;
     int* tot;
 
     __device__ __forceinline__ void init(int n_, int n_keys_, int* hist_, int* tot_) {
         n = n_;
         n_keys = n_keys_;
+        key_bits = 32 - __clz(max(n_keys_ - 1, 1));              // keys are < 2^key_bits
         hist = hist_;
         tot = tot_;
         const int n_waves = blockDim.x >> 6;
@@ -106,7 +100,7 @@ struct OrderedCounter {
         auto one_chunk = [&](int c, int key, bool in_range) {
             const bool valid = key >= 0;
             int total;
-            const int rank = wave_rank_by_key(key, valid, total);
+            const int rank = wave_rank_by_key(key, valid, key_bits, total);
             int occ = 0;
             if (valid) occ = mine[key] + rank;
             // the wave executes in lockstep: every read of mine[] above precedes the update below
