@@ -4,7 +4,7 @@
 // arxiv 2512.09277).  Every activated weight row is streamed from HBM once, with 128-bit loads that
 // land directly in the matrix-core operand layout (16 rows x 64 contiguous bytes per instruction);
 // the small, heavily reused activations are staged through LDS.  Work is cut into tiles of one
-// slot's rows:
+// slot's rows (at most 128; 32 on the smallest shapes):
 //   stream tiles (<= 32 rows at large shapes, the bulk of the bytes): per wave 2 x 16 weight rows, K steps of 128,
 //       loads issued two steps ahead so that ~128 KB per CU are in flight at 2 waves per SIMD;
 //   wide tiles (33..128 rows at large shapes, the few popular experts): per wave 4 x 16 weight rows, K steps of 64,
@@ -12,7 +12,8 @@
 //       not LDS, bound the tile; they are listed first so that they spread over the chip early.
 //   gate/up: a wave owns gate rows and the matching up rows, so silu(gate)*up is formed in
 //            registers and written once as bf16;   down: same structure over K = I.
-// A slot with no rows produces no tile and its weights are never touched.
+// A slot with no rows produces no tile and its weights are never touched.  There is no planning pass:
+// every workgroup finds its (tile, column tile) from group_offsets itself.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -43,7 +44,7 @@ struct Tile {
 __host__ __device__ inline int max_tiles(int cap, int spr, int tile_rows) { return spr + cap / tile_rows; }
 
 // ------------------------------------------------------------------------------------------ work items
-// A slot of m rows gives m / 128 full tiles and one tile for the remainder; a tile is wide if it has
+// A slot of m rows gives m / tile_rows full tiles and one tile for the remainder; a tile is wide if it has
 // more than `stream_rows` rows.  Tile order: full tiles, then the remainders by rows descending
 // (ties: lower slot first); the first n_wide of them are the wide ones.  Work item = (tile, column
 // tile), tile-major, wide items first, `ntw` column tiles per wide tile and `nts` per stream tile.
