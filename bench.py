@@ -327,6 +327,15 @@ def replication_sweep(api, torch, W, steps: int, warmup: int):
     return rows
 
 
+def optional(fn, *a, **kw):
+    """Side measurements must not take the benchmark line down with them: an exception becomes a field."""
+    try:
+        return fn(*a, **kw)
+    except Exception as e:  # noqa: BLE001 - reported, not hidden
+        print(f"bench.py: {getattr(fn, '__name__', fn)} failed: {e!r}", file=sys.stderr)
+        return {"error": repr(e)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -399,13 +408,15 @@ def main() -> int:
         g = max(per_rank, key=per_rank.get)
         hp.copies = {g: hp.copies[g]}
         ms_per_step, stage = hp.timed(g, args.steps, args.warmup)
-        graph_ms = float("nan") if args.no_hip_graph else hp.graph_ms_per_step(g)
+        graph_ms = None if args.no_hip_graph else optional(hp.graph_ms_per_step, g)
+        route_graph_us = None if args.no_hip_graph else optional(
+            graph_replay_us, torch, lambda: hp.route_fn(d_ids, d_s2e, w.N, w.G, w.spr, out=hp.rb))
         assert int(hp.rb["err_flag"].item()) == 0
         active = int(hp.rb["rank_active"][0, g].item())
         P = int(hp.pb["n_pairs"].item())
         gu_b, dn_b = algorithmic_bytes(active, P, w.H, w.I)
         ffn_us = stage["gate_up"] + stage["down"]
-        result[routing] = dict(rank=g, ms_per_step=ms_per_step, graph_ms=graph_ms, stage_us={k: round(v, 2) for k, v in stage.items()},
+        result[routing] = dict(rank=g, ms_per_step=ms_per_step, graph_ms=graph_ms, route_graph_us=route_graph_us, stage_us={k: round(v, 2) for k, v in stage.items()},
                                ffn_us=ffn_us, active=active, pairs=P, bytes=(gu_b, dn_b),
                                lam=int(hp.rb["rank_active"].max().item()),
                                per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank.items()},
@@ -428,11 +439,13 @@ def main() -> int:
                    "T": w.T, "zipf_s": w.s, "H": w.H, "I": w.I, "measured_rank": me["rank"], "routing": "metro",
                    "weight_row_pitch": {"w13": shares[me["rank"]][0].stride(1), "w2": shares[me["rank"]][1].stride(1)}},
         "route_us_per_batch": me["stage_us"]["route"],
+        "route_us_per_batch_graph_replay": {"metro": round(me["route_graph_us"], 2)
+                                            if isinstance(me["route_graph_us"], float) else me["route_graph_us"]},
         "ffn_us": {"metro": round(me["ffn_us"], 1)},
         "max_activated_per_rank": {"metro": me["lam"]},
         "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
         "stage_us": me["stage_us"],
-        "ms_per_step_hip_graph": {"metro": None if args.no_hip_graph else round(me["graph_ms"], 4)},
+        "ms_per_step_hip_graph": {"metro": round(me["graph_ms"], 4) if isinstance(me["graph_ms"], float) else me["graph_ms"]},
         "per_rank_ffn_us": {"metro": me["per_rank_ffn_us"]},
         "roofline": {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(gu_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
@@ -440,7 +453,7 @@ def main() -> int:
                      "down_kernel": {"achieved": round(dn_b / (me["stage_us"]["down"] * 1e-6) / 1e9, 1),
                                      "algorithmic_bytes_per_launch": dn_b}},
     }
-    line["gate_topk"] = gate_topk_timing(api, torch, W, w, x)
+    line["gate_topk"] = optional(gate_topk_timing, api, torch, W, w, x)
     if "token_balanced" in result:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)
@@ -448,8 +461,11 @@ def main() -> int:
         line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
         line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
         line["ms_per_step_token_balanced"] = round(tb["ms_per_step"], 4)
-        line["ms_per_step_hip_graph"]["token_balanced"] = None if args.no_hip_graph else round(tb["graph_ms"], 4)
-        line["routing_sweep"] = routing_sweep(api, torch, W, quick=False)
+        line["route_us_per_batch_graph_replay"]["token_balanced"] = (
+            round(tb["route_graph_us"], 2) if isinstance(tb["route_graph_us"], float) else tb["route_graph_us"])
+        line["ms_per_step_hip_graph"]["token_balanced"] = (round(tb["graph_ms"], 4) if isinstance(tb["graph_ms"], float)
+                                                           else tb["graph_ms"])
+        line["routing_sweep"] = optional(routing_sweep, api, torch, W, quick=False)
     if not args.no_cpu_baseline:
         from oracle import metro_oracle as oracle
 
@@ -465,7 +481,7 @@ def main() -> int:
         lam_opt = oracle.matching_opt(cnt, s2e, w.N, w.G, w.spr)
         line["cpu_baseline"]["exact_solver"] = dict(lambda_opt=int(lam_opt), lambda_metro=me["lam"],
                                                     us_per_batch_cpu=round(1e6 * (time.perf_counter() - t0), 1))
-        if "routing_sweep" in line:
+        if isinstance(line.get("routing_sweep"), list):
             line["cpu_baseline"]["routing_quality"] = routing_quality(oracle, W, line["routing_sweep"])
     print(json.dumps(line))
     return 0
