@@ -41,7 +41,9 @@ struct Tile {
     int slot, row0, rows, col;              // rows [row0, row0 + rows) of a slot x column tile `col`
 };
 
-__host__ __device__ inline int max_tiles(int cap, int spr, int tile_rows) { return spr + cap / tile_rows; }
+// Upper bound of the tile count: cap / tile_rows full tiles, and per slot one remainder or (finer one-tile
+// slots, at least half a tile each) two tiles.
+__host__ __device__ inline int max_tiles(int cap, int spr, int tile_rows) { return 2 * spr + cap / tile_rows; }
 
 // ------------------------------------------------------------------------------------------ work items
 // A slot of m rows gives m / tile_rows full tiles and one tile for the remainder; a tile is wide if it has
@@ -57,14 +59,17 @@ struct Item {
 };
 
 __device__ __forceinline__ Item locate_item(const int32_t* __restrict__ group_offsets, int spr, int cap,
-                                            int tile_rows, int stream_rows, int ntw, int nts, int id) {
+                                            int tile_rows, int single_rows, int stream_rows, int ntw, int nts,
+                                            int id) {
     const int l = lane_id();
     int begin = 0, m = 0;
     if (l < spr) {                              // offsets that are not a partition of [0, cap] are clamped
         begin = min(max(group_offsets[l], 0), cap);
         m = min(max(group_offsets[l + 1], begin), cap) - begin;
     }
-    const int full = m / tile_rows, part = m % tile_rows;
+    // one-tile slots may be cut finer than the slots that re-read their weights once per tile
+    const int th = (single_rows > 0 && m <= tile_rows) ? single_rows : tile_rows;
+    const int full = m / th, part = m % th;
     int incl = full;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -99,13 +104,14 @@ __device__ __forceinline__ Item locate_item(const int32_t* __restrict__ group_of
         const int o = __ffsll((unsigned long long)owner) - 1;
         const int first = __builtin_amdgcn_readlane(incl - full, o);
         it.tile.slot = o;
-        it.tile.row0 = __builtin_amdgcn_readlane(begin, o) + (ti - first) * tile_rows;
-        it.tile.rows = tile_rows;
+        const int th_o = __builtin_amdgcn_readlane(th, o);
+        it.tile.row0 = __builtin_amdgcn_readlane(begin, o) + (ti - first) * th_o;
+        it.tile.rows = th_o;
     } else {
         const uint64_t owner = __ballot(part > 0 && n_full + rank == ti);     // exactly one lane
         const int o = __ffsll((unsigned long long)owner) - 1;
         it.tile.slot = o;
-        it.tile.row0 = __builtin_amdgcn_readlane(begin + full * tile_rows, o);
+        it.tile.row0 = __builtin_amdgcn_readlane(begin + full * th, o);
         it.tile.rows = __builtin_amdgcn_readlane(part, o);
     }
     it.valid = it.tile.rows > 0;                // always true here; keeps a broken invariant from indexing row -1
@@ -122,6 +128,7 @@ struct FfnArgs {
     int T, k, spr, H, I;
     int ldw;                  // elements between consecutive weight rows (>= K)
     int tile_rows;            // rows of a full tile (<= 128)
+    int single_rows;          // > 0: slots of at most tile_rows rows are cut into tiles of this many rows
     int bk256;                // <= 32-row tiles take K steps of 256 with one step of prefetch
     int stream_rows;          // tiles with more rows are wide
     int ntw, nts;             // column tiles per wide / stream tile
@@ -330,7 +337,7 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     // (Measured alternatives that lost: spreading the wide items through the launch order,
     // alternating wide and stream items, and per-XCD work queues.)  Everything here is uniform per
     // workgroup.
-    const Item it = locate_item(a.group_offsets, a.spr, a.T * a.k, a.tile_rows, a.stream_rows, a.ntw, a.nts, blockIdx.x);
+    const Item it = locate_item(a.group_offsets, a.spr, a.T * a.k, a.tile_rows, a.single_rows, a.stream_rows, a.ntw, a.nts, blockIdx.x);
     if (!it.valid) return;
     const Tile t = it.tile;
     if (it.wide) ffn_tile<kGateUp, 4, 8, 64, 1>(a, t, t.col, lds);
@@ -522,6 +529,10 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     a.T = T; a.k = k; a.spr = spr; a.H = H; a.I = I;
     a.stream_rows = stream_rows_for(H, I);
     a.tile_rows = tile_rows_for(H, I);
+    // mid shapes (every tile on the stream path, 128-row tiles): a one-tile slot of 65..128 rows is the
+    // longest workgroup of a launch that has fewer workgroups than the chip has slots; two 64-row tiles
+    // balance it (token-balanced rank of the 4096 x 1536 shape: gate/up 109 -> 101 us; no gain for down)
+    a.single_rows = (a.stream_rows >= kWideRows && a.tile_rows == kWideRows) ? 64 : 0;
     a.bk256 = 0;
     a.ntw = I / 128;
     a.nts = I / 64;
@@ -563,6 +574,7 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     a.T = T; a.k = k; a.spr = spr; a.H = H; a.I = I;
     a.stream_rows = stream_rows_for(H, I);
     a.tile_rows = tile_rows_for(H, I);
+    a.single_rows = 0;
     // a short K (few steps): half as many barriers for the same bytes in flight (Qwen3-30B-shaped
     // down stage 23.2 -> 20.6 us; no gain on the gate/up stage or at I = 2048)
     a.bk256 = I % 256 == 0 && I <= 1536;

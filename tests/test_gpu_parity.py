@@ -248,10 +248,10 @@ def test_tiny_layer_all_ranks(api, oracle, dtype, tol):
                                            ("bf16", 2048, 1024, BF16_TOL),
                                            ("bf16", 200, 72, BF16_TOL), ("f32", 200, 72, F32_TOL)])
 def test_ragged_groups_span_tiles(api, oracle, dtype, H, I, tol):
-    """Groups of 0, 1, 15, 16, 17, 33, 64, 129 and 300 rows: every sub-tile count, a ragged tail,
-    a group longer than two work tiles, an empty slot.  The small shapes cut groups into 32-row
+    """Groups of 0, 1, 15, 16, 17, 33, 64, 100, 129 and 300 rows: every sub-tile count, a ragged tail,
+    a group longer than two work tiles, a one-tile group that the mid shape cuts in two, an empty slot.  The small shapes cut groups into 32-row
     tiles, (2048, 1024) into 128-row tiles on the streaming path, (200, 72) takes the general kernel."""
-    sizes = [17, 0, 1, 300, 16, 33, 129, 15, 64]
+    sizes = [17, 0, 1, 300, 16, 33, 129, 15, 64, 100]
     spr, k = len(sizes), 4
     n = sum(sizes)
     T = 200
