@@ -575,6 +575,11 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     a.stream_rows = stream_rows_for(H, I);
     a.tile_rows = tile_rows_for(H, I);
     a.single_rows = 0;
+    // mid shapes: the full 128-row tiles of a several-tile slot take the wide path in this stage (half
+    // the column tiles, each activation fragment feeding four matrix instructions); smaller tiles stay
+    // on the stream path (METRO rank of the 4096 x 1536 shape: down 71 -> 60 us; a 113-row one-tile
+    // slot on the wide path costs the token-balanced rank 8 us, hence "full tiles only")
+    if (a.stream_rows >= kWideRows && a.tile_rows == kWideRows) a.stream_rows = kWideRows - 1;
     // a short K (few steps): half as many barriers for the same bytes in flight (Qwen3-30B-shaped
     // down stage 23.2 -> 20.6 us; no gain on the gate/up stage or at I = 2048)
     a.bk256 = I % 256 == 0 && I <= 1536;
