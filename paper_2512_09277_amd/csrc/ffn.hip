@@ -41,9 +41,12 @@ struct Tile {
     int slot, row0, rows, col;              // rows [row0, row0 + rows) of a slot x column tile `col`
 };
 
-// Upper bound of the tile count: cap / tile_rows full tiles, and per slot one remainder or (finer one-tile
-// slots, at least half a tile each) two tiles.
-__host__ __device__ inline int max_tiles(int cap, int spr, int tile_rows) { return 2 * spr + cap / tile_rows; }
+// Upper bound of the tile count (the launch grid; workgroups past the real count exit after locating
+// nothing): cap / tile_rows full tiles, and per slot one remainder -- or two tiles where one-tile slots
+// are cut finer (each at least half a tile).
+inline int max_tiles(int cap, int spr, int tile_rows, bool finer_singles) {
+    return (finer_singles ? 2 : 1) * spr + cap / tile_rows;
+}
 
 // ------------------------------------------------------------------------------------------ work items
 // A slot of m rows gives m / tile_rows full tiles and one tile for the remainder; a tile is wide if it has
@@ -536,7 +539,7 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     a.bk256 = 0;
     a.ntw = I / 128;
     a.nts = I / 64;
-    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(max_tiles(cap, spr, a.tile_rows) * a.nts), dim3(kThreads), kLdsBytes, st, a);
+    hipLaunchKernelGGL(ffn_mfma_kernel<true>, dim3(max_tiles(cap, spr, a.tile_rows, a.single_rows > 0) * a.nts), dim3(kThreads), kLdsBytes, st, a);
     return launched();
 }
 
@@ -585,7 +588,7 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     a.bk256 = I % 256 == 0 && I <= 1536;
     a.ntw = (H + 255) / 256;
     a.nts = H / 128;
-    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(max_tiles(cap, spr, a.tile_rows) * a.nts), dim3(kThreads), kLdsBytes, st, a);
+    hipLaunchKernelGGL(ffn_mfma_kernel<false>, dim3(max_tiles(cap, spr, a.tile_rows, a.single_rows > 0) * a.nts), dim3(kThreads), kLdsBytes, st, a);
     return launched();
 }
 
