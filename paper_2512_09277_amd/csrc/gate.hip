@@ -128,6 +128,119 @@ __global__ __launch_bounds__(kThreads, 2) void gate_logits_mfma_kernel(GateArgs 
     }
 }
 
+// Large batches: one workgroup = 128 tokens x 128 experts x one K chunk, both operands staged through
+// LDS.  Global loads are fully coalesced (8 lanes read the 128 contiguous bytes a row contributes to a
+// K step of 64: a wave instruction covers 8 whole cache lines instead of 16 half lines), each operand
+// byte enters the CU once per workgroup, and the 2 x 2 waves (64 x 64 each, 16 accumulator tiles) read
+// their fragments from LDS in operand layout.  Double-buffered: the loads of step s + 1 are in flight
+// while step s is multiplied.
+constexpr int kBigTile = 128, kBigBK = 64;
+constexpr int kBigRow = kBigBK * 2 + 16;                         // LDS bytes per staged row (+16 spreads the banks)
+constexpr int kBigBuf = 2 * kBigTile * kBigRow;                  // x tile + w tile of one step
+constexpr int kBigLds = 2 * kBigBuf;
+
+__global__ __launch_bounds__(kThreads, 2) void gate_logits_lds_kernel(GateArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, q = lane >> 4;
+    const int chunk = blockIdx.x, t0 = blockIdx.y * kBigTile, e0 = blockIdx.z * kBigTile;
+    const int n_steps = a.H / kBigBK;                             // the host takes this path only if H % 64 == 0
+    const int s_begin = chunk * a.steps_per_chunk, s_end = min(s_begin + a.steps_per_chunk, n_steps);
+    const int last = s_end - 1;
+
+    // staging: thread (row, piece) copies 16 bytes of rows row, row + 32, row + 64, row + 96 of both tiles
+    const int srow = tid >> 3, piece = tid & 7;
+    const char* xg[4];
+    const char* wg[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int tok = min(t0 + p * 32 + srow, a.T - 1);         // rows past the batch repeat the last token
+        xg[p] = reinterpret_cast<const char*>(a.x) + ((size_t)tok * a.H) * 2 + piece * 16;
+        wg[p] = reinterpret_cast<const char*>(a.w_gate) + ((size_t)(e0 + p * 32 + srow) * a.ldw) * 2 + piece * 16;
+    }
+    const int st_off = srow * kBigRow + piece * 16;
+    // Three register sets: the loads of steps s + 1 .. s + 3 are in flight while step s is multiplied
+    // (one workgroup per CU at most at these sizes, so the prefetch distance is all the latency hiding
+    // there is).  Loads are unconditional -- past the chunk they re-read its last step -- so that the
+    // compiler counts outstanding loads exactly.
+    u32x4 xr[3][4], wr[3][4];
+    auto load = [&](int set, int s) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            xr[set][p] = *reinterpret_cast<const u32x4*>(xg[p] + (size_t)s * (kBigBK * 2));
+            wr[set][p] = *reinterpret_cast<const u32x4*>(wg[p] + (size_t)s * (kBigBK * 2));
+        }
+    };
+    auto park = [&](int set, int buf) {
+        char* base = lds + buf * kBigBuf + st_off;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            *reinterpret_cast<u32x4*>(base + p * 32 * kBigRow) = xr[set][p];
+            *reinterpret_cast<u32x4*>(base + kBigTile * kBigRow + p * 32 * kBigRow) = wr[set][p];
+        }
+    };
+
+    const int ty = wv >> 1, tx = wv & 1;                          // wave: tokens [64 ty, +64), experts [64 tx, +64)
+    const int rd = r16 * kBigRow + q * 16;
+    floatx4 acc[4][4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) acc[b][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // step U of a period of 6 (register set U % 3, LDS buffer U % 2 known at compile time)
+    auto step = [&](auto Uc, int s) {
+        constexpr int U = decltype(Uc)::value;
+        load(U % 3, min(s + 3, last));                            // set U % 3 was parked one step ago
+        const char* xt = lds + (U % 2) * kBigBuf + ty * 64 * kBigRow + rd;
+        const char* wt = lds + (U % 2) * kBigBuf + kBigTile * kBigRow + tx * 64 * kBigRow + rd;
+#pragma unroll
+        for (int j = 0; j < kBigBK / 32; ++j) {
+            bf16x8 xb[4], wa[4];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) xb[mt] = *reinterpret_cast<const bf16x8*>(xt + mt * 16 * kBigRow + j * 64);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) wa[b] = *reinterpret_cast<const bf16x8*>(wt + b * 16 * kBigRow + j * 64);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+                    acc[b][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[b], xb[mt], acc[b][mt], 0, 0, 0);
+        }
+        park((U + 1) % 3, (U + 1) % 2);                           // step s + 1, loaded two steps ago
+        __syncthreads();
+    };
+    load(0, min(s_begin, last));
+    load(1, min(s_begin + 1, last));
+    load(2, min(s_begin + 2, last));
+    park(0, 0);
+    __syncthreads();
+    int s = s_begin;
+    for (; s + 6 <= s_end; s += 6) {
+        step(std::integral_constant<int, 0>{}, s);
+        step(std::integral_constant<int, 1>{}, s + 1);
+        step(std::integral_constant<int, 2>{}, s + 2);
+        step(std::integral_constant<int, 3>{}, s + 3);
+        step(std::integral_constant<int, 4>{}, s + 4);
+        step(std::integral_constant<int, 5>{}, s + 5);
+    }
+    // tail: at most five steps; once one is past the end nothing after it is tested
+    (void)((s + 0 < s_end && (step(std::integral_constant<int, 0>{}, s + 0), true)) &&
+           (s + 1 < s_end && (step(std::integral_constant<int, 1>{}, s + 1), true)) &&
+           (s + 2 < s_end && (step(std::integral_constant<int, 2>{}, s + 2), true)) &&
+           (s + 3 < s_end && (step(std::integral_constant<int, 3>{}, s + 3), true)) &&
+           (s + 4 < s_end && (step(std::integral_constant<int, 4>{}, s + 4), true)));
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int t = t0 + ty * 64 + mt * 16 + r16;
+        if (t < a.T) {
+            float* out = a.part + ((size_t)chunk * a.T + t) * a.N + e0 + tx * 64 + q * 4;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) *reinterpret_cast<floatx4*>(out + b * 16) = acc[b][mt];
+        }
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ float elem_f32(const void* p, size_t i);
 template <>
@@ -248,11 +361,23 @@ inline bool gate_mfma_shape(int H, int N, int dtype) {
     return dtype == METRO_DTYPE_BF16 && H % 32 == 0 && N % kExpTile == 0 && N <= kMaxN;
 }
 
+// The LDS-staged kernel takes batches of at least 1024 tokens when N % 128 == 0 and H % 64 == 0 (measured
+// against the direct kernel at N = 256, H = 7168: 17.0 vs 18.7 us at T = 1024, 28 vs 56 us at T = 4096;
+// below that the direct kernel's smaller workgroups win).
+inline bool gate_big(int T, int H, int N) { return T >= 1024 && N % kBigTile == 0 && H % kBigBK == 0; }
+
 // Tokens per workgroup: 64 (four sub-tiles) unless the batch is a single sub-tile.
 inline int gate_tok_tile(int T) { return T > kTokTile ? 4 * kTokTile : kTokTile; }
 
 // K chunks: enough workgroups for two per CU (~512), each chunk at least kMinChunkSteps steps per wave.
 inline int gate_steps_per_chunk(int T, int H, int N) {
+    if (gate_big(T, H, N)) {                    // steps of 64; ~8 chunks (one K range per XCD), >= 4 steps each
+        const int n_steps = H / kBigBK;
+        const int tiles = ((T + kBigTile - 1) / kBigTile) * (N / kBigTile);
+        const int want = tiles * 8 < 256 ? 16 : 8;               // at least one workgroup per CU
+        int chunks = n_steps / 4 >= want ? want : n_steps / 4 >= 8 ? 8 : n_steps / 4 > 0 ? n_steps / 4 : 1;
+        return (n_steps + chunks - 1) / chunks;
+    }
     const int n_steps = H / 32, tile = gate_tok_tile(T);
     const int tiles = ((T + tile - 1) / tile) * (N / kExpTile);
     int chunks = (512 + tiles - 1) / tiles;
@@ -265,7 +390,8 @@ inline int gate_steps_per_chunk(int T, int H, int N) {
 inline int gate_chunks(int T, int H, int N, int dtype) {
     if (!gate_mfma_shape(H, N, dtype)) return 1;
     const int spc = gate_steps_per_chunk(T, H, N);
-    return (H / 32 + spc - 1) / spc;
+    const int n_steps = gate_big(T, H, N) ? H / kBigBK : H / 32;
+    return (n_steps + spc - 1) / spc;
 }
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -302,13 +428,25 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, 
     int n_chunks = 1;
     if (mfma) {
         a.steps_per_chunk = gate_steps_per_chunk(T, H, N);
-        n_chunks = (H / 32 + a.steps_per_chunk - 1) / a.steps_per_chunk;
+        n_chunks = gate_chunks(T, H, N, dtype);
+        if (gate_big(T, H, N)) {
+            static bool lds_ok = false;                           // opt in to > 64 KB of dynamic LDS, once
+            if (!lds_ok) {
+                if (hipFuncSetAttribute((const void*)gate_logits_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kBigLds) != hipSuccess)
+                    return METRO_ERR_HIP;
+                lds_ok = true;
+            }
+            const dim3 grid(n_chunks, (T + kBigTile - 1) / kBigTile, N / kBigTile);
+            hipLaunchKernelGGL(gate_logits_lds_kernel, grid, dim3(kThreads), kBigLds, st, a);
+        } else {
         const int tile = gate_tok_tile(T);
         const dim3 grid(n_chunks, (T + tile - 1) / tile, N / kExpTile);
         if (tile == kTokTile)
             hipLaunchKernelGGL(gate_logits_mfma_kernel<1>, grid, dim3(kThreads), 0, st, a);
         else
             hipLaunchKernelGGL(gate_logits_mfma_kernel<4>, grid, dim3(kThreads), 0, st, a);
+        }
     }
     if (!mfma) {
         a.steps_per_chunk = 0;

@@ -65,7 +65,9 @@ CASES = [  # T, H, N, k, dtype, padded rows
     (256, 2048, 128, 8, "bf16", 0),
     (1024, 7168, 256, 8, "bf16", 0),     # DeepSeek-V3-shaped router at the benchmark's batch
     (1024, 7168, 256, 8, "bf16", 64),    # the same with padded weight rows
-    (19, 96, 512, 6, "bf16", 0),         # eight blocks per wave
+    (1100, 512, 128, 8, "bf16", 0),      # LDS-staged kernel (T >= 1024), ragged last token tile
+    (1030, 128, 384, 5, "bf16", 64),     # LDS-staged kernel, one K chunk of two steps, three expert tiles, padded rows
+    (19, 96, 512, 6, "bf16", 0),         # direct kernel, eight expert tiles
     (9, 200, 192, 3, "bf16", 0),         # H and N the matrix-core kernel does not take
     (3, 128, 64, 64, "bf16", 0),         # k = N = 64: everything selected
 ]
