@@ -142,7 +142,10 @@ class HotPath:
         torch.cuda.synchronize()
         wall_ms = 1e3 * (time.perf_counter() - t0)
         dev_ms = evs[0][0].elapsed_time(evs[-1][5])
-        stage = {n: 1e3 * float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, n in ((2, "gate_up"), (3, "down"))}
+        per_step = {n: np.array([1e3 * e[i].elapsed_time(e[i + 1]) for e in evs]) for i, n in ((2, "gate_up"), (3, "down"))}
+        stage = {n: float(v.mean()) for n, v in per_step.items()}
+        ffn = per_step["gate_up"] + per_step["down"]
+        self.ffn_quantiles = [round(float(np.percentile(ffn, q)), 1) for q in (10, 50, 90)]
         full = [[ev() for _ in range(6)] for _ in range(min(steps, 20))]
         for e in full:
             self.step(g, e)
@@ -416,7 +419,7 @@ def main() -> int:
         P = int(hp.pb["n_pairs"].item())
         gu_b, dn_b = algorithmic_bytes(active, P, w.H, w.I)
         ffn_us = stage["gate_up"] + stage["down"]
-        result[routing] = dict(rank=g, ms_per_step=ms_per_step, graph_ms=graph_ms, route_graph_us=route_graph_us, stage_us={k: round(v, 2) for k, v in stage.items()},
+        result[routing] = dict(rank=g, ms_per_step=ms_per_step, ffn_q=hp.ffn_quantiles, graph_ms=graph_ms, route_graph_us=route_graph_us, stage_us={k: round(v, 2) for k, v in stage.items()},
                                ffn_us=ffn_us, active=active, pairs=P, bytes=(gu_b, dn_b),
                                lam=int(hp.rb["rank_active"].max().item()),
                                per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank.items()},
@@ -442,6 +445,7 @@ def main() -> int:
         "route_us_per_batch_graph_replay": {"metro": round(me["route_graph_us"], 2)
                                             if isinstance(me["route_graph_us"], float) else me["route_graph_us"]},
         "ffn_us": {"metro": round(me["ffn_us"], 1)},
+        "ffn_us_p10_p50_p90": {"metro": me["ffn_q"]},
         "max_activated_per_rank": {"metro": me["lam"]},
         "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
         "stage_us": me["stage_us"],
@@ -457,6 +461,12 @@ def main() -> int:
     if "token_balanced" in result:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)
+        line["ffn_us_p10_p50_p90"]["token_balanced"] = tb["ffn_q"]
+        # the comparison is only worth stating when the gap exceeds the run-to-run spread of both sides
+        gap = abs(me["ffn_q"][1] - tb["ffn_q"][1])
+        spread = max(me["ffn_q"][2] - me["ffn_q"][0], tb["ffn_q"][2] - tb["ffn_q"][0])
+        line["metro_vs_token_balanced"] = {"ffn_time_ratio": round(me["ffn_q"][1] / tb["ffn_q"][1], 3),
+                                           "conclusive": bool(gap > spread)}
         line["max_activated_per_rank"]["token_balanced"] = tb["lam"]
         line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
         line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
