@@ -462,6 +462,10 @@ def main() -> int:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)
         line["ffn_us_p10_p50_p90"]["token_balanced"] = tb["ffn_q"]
+        tb_gu = tb["bytes"][0] / (tb["stage_us"]["gate_up"] * 1e-6) / 1e9
+        line["roofline"]["same_kernel_on_token_balanced_rank"] = {
+            "achieved": round(tb_gu, 1), "frac": round(tb_gu / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": tb["bytes"][0], "pairs": tb["pairs"]}
         # the comparison is only worth stating when the gap exceeds the run-to-run spread of both sides
         gap = abs(me["ffn_q"][1] - tb["ffn_q"][1])
         spread = max(me["ffn_q"][2] - me["ffn_q"][0], tb["ffn_q"][2] - tb["ffn_q"][0])
