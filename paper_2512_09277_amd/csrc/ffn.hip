@@ -343,7 +343,11 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
     const Item it = locate_item(a.group_offsets, a.spr, a.T * a.k, a.tile_rows, a.single_rows, a.stream_rows, a.ntw, a.nts, blockIdx.x);
     if (!it.valid) return;
     const Tile t = it.tile;
-    if (it.wide) ffn_tile<kGateUp, 4, 8, 64, 1>(a, t, t.col, lds);
+    // partial wide tiles stage only the rows they have; with half the accumulators the 64-row variant
+    // also affords a second K step of weights in flight (token-balanced rank: gate/up 401 -> 390 us)
+    if (it.wide && t.rows <= 64) ffn_tile<kGateUp, 4, 4, 64, 2>(a, t, t.col, lds);
+    else if (it.wide && t.rows <= 96) ffn_tile<kGateUp, 4, 6, 64, 1>(a, t, t.col, lds);
+    else if (it.wide) ffn_tile<kGateUp, 4, 8, 64, 1>(a, t, t.col, lds);
     else if (t.rows <= 32 && a.bk256) {
         if (t.rows <= 16) ffn_tile<kGateUp, 2, 1, 256, 1>(a, t, t.col, lds);
         else ffn_tile<kGateUp, 2, 2, 256, 1>(a, t, t.col, lds);
