@@ -21,6 +21,7 @@
 #include <utility>
 
 #include "device_utils.h"
+#include "host_utils.h"
 #include "metro.h"
 
 namespace metro {
@@ -462,17 +463,16 @@ int check_common(const int32_t* group_offsets, int T, int k, int spr, int H, int
     return METRO_OK;
 }
 
-int enable_large_lds() {                            // opt in to > 64 KB of dynamic LDS, once
-    static bool done = false;
-    if (!done) {
-        if (hipFuncSetAttribute((const void*)ffn_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes) != hipSuccess ||
-            hipFuncSetAttribute((const void*)ffn_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes) != hipSuccess)
-            return METRO_ERR_HIP;
-        done = true;
-    }
-    return METRO_OK;
+int enable_large_lds() {                            // opt in to > 64 KB of dynamic LDS, once per device
+    static PerDeviceOnce once;
+    return once.run([] {
+        hipError_t e = hipFuncSetAttribute((const void*)ffn_mfma_kernel<true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)ffn_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kLdsBytes);
+        return e;
+    });
 }
 
 // Remainders of at most this many rows become stream tiles.  A wide workgroup prefetches one step

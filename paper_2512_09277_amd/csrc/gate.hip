@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "device_utils.h"
+#include "host_utils.h"
 #include "metro.h"
 
 namespace metro {
@@ -430,13 +431,12 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, 
         a.steps_per_chunk = gate_steps_per_chunk(T, H, N);
         n_chunks = gate_chunks(T, H, N, dtype);
         if (gate_big(T, H, N)) {
-            static bool lds_ok = false;                           // opt in to > 64 KB of dynamic LDS, once
-            if (!lds_ok) {
-                if (hipFuncSetAttribute((const void*)gate_logits_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        kBigLds) != hipSuccess)
-                    return METRO_ERR_HIP;
-                lds_ok = true;
-            }
+            static PerDeviceOnce lds_ok;                          // opt in to > 64 KB of dynamic LDS, once per device
+            if (lds_ok.run([] {
+                    return hipFuncSetAttribute((const void*)gate_logits_lds_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+                }) != METRO_OK)
+                return METRO_ERR_HIP;
             const dim3 grid(n_chunks, (T + kBigTile - 1) / kBigTile, N / kBigTile);
             hipLaunchKernelGGL(gate_logits_lds_kernel, grid, dim3(kThreads), kBigLds, st, a);
         } else {
