@@ -342,8 +342,8 @@ def optional(fn, *a, **kw):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="deepseek_v3_decode")
     ap.add_argument("--rank", type=int, default=-1, help="pin the measured rank (skips the per-rank search)")
     ap.add_argument("--only-metro", action="store_true", help="skip the token-balanced comparison and the sweep")
