@@ -347,6 +347,9 @@ def main() -> int:
     ap.add_argument("--workload", default="deepseek_v3_decode")
     ap.add_argument("--rank", type=int, default=-1, help="pin the measured rank (skips the per-rank search)")
     ap.add_argument("--only-metro", action="store_true", help="skip the token-balanced comparison and the sweep")
+    ap.add_argument("--only-token-balanced", action="store_true",
+                    help="run the path under token-balanced routing only and print a reduced line (for profiling "
+                         "the baseline's rank with rocprofv3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle FFN work")
     ap.add_argument("--dense-weights", action="store_true",
@@ -405,7 +408,8 @@ def main() -> int:
         del src, dst
 
     result = {}
-    for routing in (("metro",) if args.only_metro else ("metro", "token_balanced")):
+    routings = ("token_balanced",) if args.only_token_balanced else ("metro",) if args.only_metro else ("metro", "token_balanced")
+    for routing in routings:
         hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
         per_rank = {g: hp.ffn_only_us(g) for g in ranks}
         g = max(per_rank, key=per_rank.get)
@@ -424,6 +428,12 @@ def main() -> int:
                                lam=int(hp.rb["rank_active"].max().item()),
                                per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank.items()},
                                perm={k: v.cpu().numpy() for k, v in hp.pb.items()})
+    if args.only_token_balanced:
+        tb = result["token_balanced"]
+        print(json.dumps({"mode": "token_balanced_only", "workload": w.name, "steps": args.steps, "rank": tb["rank"],
+                          "activated": tb["active"], "pairs": tb["pairs"], "stage_us": tb["stage_us"],
+                          "algorithmic_bytes_per_launch": {"gate_up": tb["bytes"][0], "down": tb["bytes"][1]}}))
+        return 0
     me = result["metro"]
     gu_b, dn_b = me["bytes"]
     ffn_gbs = (gu_b + dn_b) / (me["ffn_us"] * 1e-6) / 1e9
