@@ -384,7 +384,7 @@ def test_empty_rank_ffn(api):
     assert (y == 3.0).all() and (out == 0).all()
 
 
-@pytest.mark.parametrize("w", [W.QWEN3_30B, W.DSV3], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [W.QWEN3_30B, W.QWEN3_235B, W.DSV3], ids=lambda w: w.name)
 def test_full_size_sampled_rows(api, oracle, w):
     """Full shapes in the launch configuration the benchmark times: the busiest METRO rank, weights
     drawn on the device; the oracle recomputes sampled rows (first/last row of the widest group,
