@@ -384,17 +384,20 @@ def test_empty_rank_ffn(api):
     assert (y == 3.0).all() and (out == 0).all()
 
 
-@pytest.mark.parametrize("w", [W.QWEN3_30B, W.QWEN3_235B, W.DSV3], ids=lambda w: w.name)
-def test_full_size_sampled_rows(api, oracle, w):
-    """Full shapes in the launch configuration the benchmark times: the busiest METRO rank, weights
-    drawn on the device; the oracle recomputes sampled rows (first/last row of the widest group,
-    of a one-tile group, and random rows) from host copies of the same bytes."""
+@pytest.mark.parametrize("w,routing", [(W.QWEN3_30B, "metro"), (W.QWEN3_235B, "metro"), (W.DSV3, "metro"),
+                                       (W.DSV3, "token_balanced")], ids=lambda v: getattr(v, "name", v))
+def test_full_size_sampled_rows(api, oracle, w, routing):
+    """Full shapes in the launch configuration the benchmark times: the busiest rank under the given
+    routing, weights drawn on the device; the oracle recomputes sampled rows (first/last row of the
+    widest group, of a one-tile group, and random rows) from host copies of the same bytes."""
     import torch
 
     _, s2e, ids = W.routing_inputs(w)
-    out = api.metro_route(dev_i32(ids), dev_i32(s2e), w.N, w.G, w.spr)
+    route, route_ref = ((api.metro_route, oracle.route_metro) if routing == "metro" else
+                        (api.metro_route_token_balanced, oracle.route_token_balanced))
+    out = route(dev_i32(ids), dev_i32(s2e), w.N, w.G, w.spr)
     ps = out["pair_slot"][0].cpu().numpy()
-    ref = oracle.route_metro(ids, s2e, w.N, w.G, w.spr)
+    ref = route_ref(ids, s2e, w.N, w.G, w.spr)
     assert np.array_equal(ps, ref["pair_slot"])
     g = int(np.argmax(np.bincount(ps.reshape(-1) // w.spr, minlength=w.G)))
     print(f"full size {w.name}: rank {g}", flush=True)
