@@ -384,6 +384,33 @@ def test_empty_rank_ffn(api):
     assert (y == 3.0).all() and (out == 0).all()
 
 
+@pytest.mark.parametrize("dtype,H,I", [("bf16", 256, 128), ("f32", 200, 72)])
+def test_malformed_lists_stay_in_bounds(api, dtype, H, I):
+    """group_offsets that are no partition of the rows and perm_pair entries that are no pair index are
+    clamped by the kernels (every row index stays below T*k, every token below T, every slot below spr):
+    the call must not touch memory past its buffers.  Checked with guard regions after y_perm and after
+    the workspace; the results of such a call are unspecified."""
+    import torch
+
+    T, k, spr = 40, 4, 6
+    cap = T * k
+    x = dev_fp(W.activations(T, H, 71, dtype))
+    w13, w2 = (dev_fp(a) for a in W.expert_weights(spr, H, I, 72, dtype))
+    guard = 64
+    y_buf = torch.full((cap + guard, H), 7.0, dtype=x.dtype, device="cuda")
+    need = api.moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, x.dtype)
+    ws_buf = torch.full((need + 4096,), 0x5A, dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(73)
+    for go in ([0, 50, 20, 10**9, -7, 90, cap + 1000], [cap] * (spr + 1), [-5] * (spr + 1),
+               [0, cap, 0, cap, 0, cap, 0], rng.integers(-300, 600, size=spr + 1).tolist()):
+        pp = rng.integers(-10**6, 10**6, size=cap)
+        print(f"malformed offsets {go}", flush=True)
+        api.moe_grouped_ffn(x, dev_i32(pp), dev_i32(go), k, w13, w2, y_perm=y_buf[:cap], ws=ws_buf[:need])
+        torch.cuda.synchronize()
+        assert (y_buf[cap:] == 7.0).all(), "wrote past y_perm"
+        assert (ws_buf[need:] == 0x5A).all(), "wrote past the workspace"
+
+
 @pytest.mark.parametrize("w,routing", [(W.QWEN3_30B, "metro"), (W.QWEN3_235B, "metro"), (W.DSV3, "metro"),
                                        (W.DSV3, "token_balanced")], ids=lambda v: getattr(v, "name", v))
 def test_full_size_sampled_rows(api, oracle, w, routing):
