@@ -169,6 +169,7 @@ int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, int spr, in
  * accumulated in fp32; tokens with no pair on this rank get zeros.
  *
  *   y_perm [T*k,H] dtype, pair_row [T,k] int32, topk_w [T,k] float32, out [T,H] dtype.
+ *   An entry of pair_row outside [0, T*k) counts as "not on this rank".
  */
 int moe_unpermute(const void* y_perm, const int32_t* pair_row, const float* topk_w, int T, int k, int H,
                   int dtype, void* out, void* stream);

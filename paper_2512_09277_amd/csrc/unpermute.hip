@@ -26,6 +26,7 @@ __global__ __launch_bounds__(kThreads) void unpermute_bf16x8_kernel(const uint4*
                                                                     const float* __restrict__ topk_w, int k, int H8,
                                                                     uint4* __restrict__ out) {
     const int t = blockIdx.x;
+    const int cap = (int)gridDim.x * k;           // rows of y_perm; an entry of pair_row outside [0, cap) is skipped
     auto add = [](float (&acc)[8], float w, const uint4& v) {
         const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -48,6 +49,7 @@ __global__ __launch_bounds__(kThreads) void unpermute_bf16x8_kernel(const uint4*
 #pragma unroll
         for (int j = 0; j < KMAX; ++j) {
             rows[j] = j < k ? pair_row[(size_t)t * k + j] : -1;
+            if (rows[j] >= cap) rows[j] = -1;
             ws[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
         }
         for (int c = threadIdx.x; c < H8; c += kThreads) {
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(kThreads) void unpermute_bf16x8_kernel(const uint4*
             float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             for (int j = 0; j < k; ++j) {
                 const int r = pair_row[(size_t)t * k + j];
-                if (r < 0) continue;
+                if (r < 0 || r >= cap) continue;
                 add(acc, topk_w[(size_t)t * k + j], y[(size_t)r * H8 + c]);
             }
             out[(size_t)t * H8 + c] = pack(acc);
@@ -80,11 +82,12 @@ __global__ __launch_bounds__(kThreads) void unpermute_scalar_kernel(const void* 
                                                                     const float* __restrict__ topk_w, int k, int H,
                                                                     void* __restrict__ out) {
     const int t = blockIdx.x;
+    const int cap = (int)gridDim.x * k;
     for (int c = threadIdx.x; c < H; c += kThreads) {
         float acc = 0.f;
         for (int j = 0; j < k; ++j) {
             const int r = pair_row[(size_t)t * k + j];
-            if (r < 0) continue;
+            if (r < 0 || r >= cap) continue;
             const float v = kBf16 ? bf16_bits_to_f32(((const uint16_t*)y)[(size_t)r * H + c])
                                   : ((const float*)y)[(size_t)r * H + c];
             acc = fmaf(topk_w[(size_t)t * k + j], v, acc);

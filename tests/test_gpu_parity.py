@@ -409,6 +409,17 @@ def test_malformed_lists_stay_in_bounds(api, dtype, H, I):
         torch.cuda.synchronize()
         assert (y_buf[cap:] == 7.0).all(), "wrote past y_perm"
         assert (ws_buf[need:] == 0x5A).all(), "wrote past the workspace"
+    # the combine skips rows outside [0, T*k)
+    out_buf = torch.full((T + 8, H), 7.0, dtype=x.dtype, device="cuda")
+    pr = rng.integers(-10**6, 10**6, size=(T, k))
+    pr[0] = [0, cap - 1, cap, -1]
+    tw = torch.ones((T, k), dtype=torch.float32, device="cuda")
+    y_buf[:cap] = 1.0
+    api.moe_unpermute(y_buf[:cap], dev_i32(pr), tw, out=out_buf[:T])
+    torch.cuda.synchronize()
+    assert (out_buf[T:] == 7.0).all(), "wrote past out"
+    valid = ((pr >= 0) & (pr < cap)).sum(axis=1)
+    assert valid[0] == 2 and np.array_equal(host_f64(out_buf[:T])[:, 0], valid.astype(np.float64))
 
 
 @pytest.mark.parametrize("w,routing", [(W.QWEN3_30B, "metro"), (W.QWEN3_235B, "metro"), (W.DSV3, "metro"),
