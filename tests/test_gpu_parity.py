@@ -124,6 +124,37 @@ def test_routing_random_edge_cases(api, oracle, seed):
     check_routing(api, oracle, ids, s2e, N, G, spr)
 
 
+def test_largest_batch_routing_and_token_lists(api, oracle):
+    """T*k = 2^24 - 8, the largest batch the calls accept (the DeepSeek-V3 placement shape): both routers
+    and the token lists of one rank, bit for bit; one more token is refused on the host."""
+    import torch
+
+    N, G, spr, k = 256, 8, 36, 8
+    T = (1 << 21) - 1
+    rng = np.random.default_rng(99)
+    s2e = np.full(G * spr, -1, np.int32)
+    order = rng.permutation(G * spr)
+    s2e[order[:N]] = rng.permutation(N)
+    s2e[order[N:]] = rng.choice(N, size=G * spr - N, replace=False)        # 32 second replicas
+    # k distinct experts per token: an arithmetic progression with an odd step modulo N (a power of two)
+    base, step = rng.integers(0, N, size=(T, 1)), 2 * rng.integers(0, N // 2, size=(T, 1)) + 1
+    ids = ((base + step * np.arange(k)) % N).astype(np.int32)
+    ids[rng.random((T, k)) < 0.01] = -1
+    print(f"largest batch: T={T} k={k}", flush=True)
+    me, tb = check_routing(api, oracle, ids[None], s2e[None], N, G, spr)
+    for ps in (me["pair_slot"][0], tb["pair_slot"][0]):
+        g = 3
+        pm = api.moe_permute(dev_i32(ps), g, spr)
+        ref = oracle.permute(ps, g, spr)
+        n = ref["n_pairs"]
+        assert int(pm["n_pairs"].item()) == n
+        assert np.array_equal(pm["group_offsets"].cpu().numpy(), ref["group_offsets"])
+        assert np.array_equal(pm["perm_pair"].cpu().numpy()[:n], ref["perm_pair"])
+        assert np.array_equal(pm["pair_row"].cpu().numpy(), ref["pair_row"])
+    with pytest.raises(api.MetroError):
+        api.metro_route(torch.zeros((1, T + 1, k), dtype=torch.int32, device="cuda"), dev_i32(s2e[None]), N, G, spr)
+
+
 def test_routing_is_deterministic(api):
     w = W.DSV3_SWEEP
     s2e, ids = W.routing_inputs_layers(w.with_(layers=8), T=1024)
