@@ -113,7 +113,7 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
  *          N % 64 == 0, ldw % 8 == 0 and x, w_gate are 16-byte aligned; other shapes and
  *          METRO_DTYPE_F32 take a plain fp32 kernel.  Logits are summed in a fixed order, so the
  *          result is deterministic; NaN logits sort below every number.
- * Limits: N <= 512, k <= min(N, 64), T*k < 2^24.  T == 0 is a no-op.
+ * Limits: N <= 512, k <= min(N, 64), T*k < 2^24.  T == 0 writes nothing but expert_count (all zero).
  */
 size_t moe_gate_topk_workspace_bytes(int T, int H, int N, int dtype);
 int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, int H, int N, int k, int dtype,

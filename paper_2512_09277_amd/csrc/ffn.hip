@@ -140,8 +140,11 @@ struct FfnArgs {
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    ua += 0x7fffu + ((ua >> 16) & 1u);       // round to nearest even
-    ub += 0x7fffu + ((ub >> 16) & 1u);
+    const uint32_t ra = ua + 0x7fffu + ((ua >> 16) & 1u);       // round to nearest even
+    const uint32_t rb = ub + 0x7fffu + ((ub >> 16) & 1u);
+    // NaN stays a (quiet) NaN: the rounding add could carry its mantissa into Inf or -0
+    ua = (a != a) ? (ua | 0x00400000u) : ra;
+    ub = (b != b) ? (ub | 0x00400000u) : rb;
     return (ua >> 16) | (ub & 0xffff0000u);
 }
 

@@ -414,7 +414,14 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, 
     if (dtype != METRO_DTYPE_BF16 && dtype != METRO_DTYPE_F32) return METRO_ERR_UNSUPPORTED;
     if (N > kMaxN || k > kWave || (int64_t)T * k >= (1 << 24)) return METRO_ERR_UNSUPPORTED;
     if (ldw < H) return METRO_ERR_INVALID_ARG;
-    if (T == 0) return METRO_OK;
+    if (T == 0) {                                                 // no token: every expert counts zero pairs
+        if (expert_count) {
+            hipLaunchKernelGGL(gate_count_kernel, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream,
+                               (const int32_t*)nullptr, 0, N, expert_count);
+            if (hipGetLastError() != hipSuccess) return METRO_ERR_HIP;
+        }
+        return METRO_OK;
+    }
     if (!x || !w_gate || !topk_ids || !topk_w || !ws) return METRO_ERR_INVALID_ARG;
     if (((uintptr_t)ws & 255) != 0) return METRO_ERR_INVALID_ARG;
     if (ws_bytes < moe_gate_topk_workspace_bytes(T, H, N, dtype)) return METRO_ERR_WORKSPACE;

@@ -13,7 +13,8 @@ constexpr int kThreads = 256;
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float v) {
     uint32_t u = __float_as_uint(v);
-    u += 0x7fffu + ((u >> 16) & 1u);
+    if (v != v) return (u >> 16) | 0x0040u;   // NaN stays a (quiet) NaN: the rounding add could carry it into Inf or -0
+    u += 0x7fffu + ((u >> 16) & 1u);          // round to nearest even
     return u >> 16;
 }
 

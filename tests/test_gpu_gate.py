@@ -121,3 +121,17 @@ def test_gate_feeds_the_routing_solve(api, oracle):
     ref = oracle.route_metro(ids.cpu().numpy(), s2e, w.N, w.G, w.spr)
     assert np.array_equal(out["pair_slot"][0].cpu().numpy(), ref["pair_slot"])
     assert np.array_equal(got["expert_count"].cpu().numpy(), oracle.count(ids.cpu().numpy(), w.N))
+
+
+def test_empty_batch_zeroes_the_counts(api):
+    """T == 0: no id or weight is written, and expert_count -- which a caller reuses across batches -- is zero."""
+    import torch
+
+    H, N, k = 64, 64, 4
+    out = dict(topk_ids=torch.empty((0, k), dtype=torch.int32, device="cuda"),
+               topk_w=torch.empty((0, k), dtype=torch.float32, device="cuda"),
+               expert_count=torch.full((N,), 7, dtype=torch.int32, device="cuda"))
+    x = torch.empty((0, H), dtype=torch.bfloat16, device="cuda")
+    api.moe_gate_topk(x, dev(W.gate_weights(N, H, 81, "bf16")), k, out=out)
+    torch.cuda.synchronize()
+    assert (out["expert_count"] == 0).all()

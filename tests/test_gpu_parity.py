@@ -3,7 +3,10 @@
 Integer outputs (routing, permutation) must match bit for bit.  FFN outputs are compared with
     err = max|gpu - ref| / max|ref|      over the output tensor,
 within 2e-2 for bf16 storage (the kernel rounds silu(gate)*up and y to bf16; the oracle never
-rounds) and 1e-5 for fp32.
+rounds) and 1e-5 for fp32.  That is the contract.  Every-row comparisons also hold the kernels to what
+the arithmetic actually gives (see check_close): the tensor-wide error within half the contract, the same
+measure taken row by row (a wrong row cannot hide behind a larger one), and the element-wise relative
+error with the denominator floored at 1e-3 * max|ref| reported and bounded at its 99.9th percentile.
 """
 import numpy as np
 import pytest
@@ -50,6 +53,34 @@ def host_f64(t):
 
 def rel_err(got, ref):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def error_metrics(got, ref):
+    """tensor-wide max|d|/max|ref|; the same per row (rows of at most 1e-6 of the tensor's scale are measured
+    against that scale); element-wise |d|/max(|ref|, 1e-3 max|ref|): its maximum and 99.9th percentile."""
+    d = np.abs(got - ref)
+    scale = max(float(np.abs(ref).max()), 1e-30)
+    row_scale = np.maximum(np.abs(ref).reshape(ref.shape[0], -1).max(axis=1), 1e-6 * scale)
+    elem = d / np.maximum(np.abs(ref), 1e-3 * scale)
+    return dict(tensor=float(d.max() / scale), row=float((d.reshape(d.shape[0], -1).max(axis=1) / row_scale).max()),
+                elem_max=float(elem.max()), elem_p999=float(np.quantile(elem, 0.999)))
+
+
+def check_close(got, ref, tol, what):
+    """The contract (tensor-wide error <= tol) and the tighter bounds the arithmetic supports: two bf16
+    roundings (relative 2^-9 each) on sums of hundreds to thousands of terms leave a tensor-wide error of a few
+    1e-3, so half the contract must hold tensor-wide and the whole contract row by row; an element no smaller
+    than 1e-3 of the tensor's scale is off by less than 20 % in 999 cases of 1000 (the few elements near that
+    floor carry the same absolute error as the large ones, so the maximum of this measure is reported only)."""
+    if got.size == 0:
+        return None
+    m = error_metrics(got, ref)
+    print(f"{what}: tensor {m['tensor']:.2e} per-row {m['row']:.2e} element-wise max {m['elem_max']:.2e} "
+          f"p99.9 {m['elem_p999']:.2e} (contract {tol:.0e})", flush=True)
+    assert m["tensor"] <= tol / 2, f"{what}: tensor-wide error {m['tensor']}"
+    assert m["row"] <= tol, f"{what}: per-row error {m['row']}"
+    assert m["elem_p999"] <= 10 * tol, f"{what}: element-wise p99.9 {m['elem_p999']}"
+    return m
 
 
 def check_routing(api, oracle, ids, s2e, N, G, spr):
@@ -161,9 +192,13 @@ def test_routing_is_deterministic(api):
     d_ids, d_s2e = dev_i32(ids), dev_i32(s2e)
     first = api.metro_route(d_ids, d_s2e, w.N, w.G, w.spr)["pair_slot"].clone()
     first_tb = api.metro_route_token_balanced(d_ids, d_s2e, w.N, w.G, w.spr)["pair_slot"].clone()
-    for _ in range(200):
-        assert (api.metro_route(d_ids, d_s2e, w.N, w.G, w.spr)["pair_slot"] == first).all()
-        assert (api.metro_route_token_balanced(d_ids, d_s2e, w.N, w.G, w.spr)["pair_slot"] == first_tb).all()
+    import torch
+
+    bad = torch.zeros((), dtype=torch.int64, device="cuda")
+    for _ in range(1000):                                       # mismatches accumulate on the device: no sync per call
+        bad += (api.metro_route(d_ids, d_s2e, w.N, w.G, w.spr)["pair_slot"] != first).sum()
+        bad += (api.metro_route_token_balanced(d_ids, d_s2e, w.N, w.G, w.spr)["pair_slot"] != first_tb).sum()
+    assert int(bad.item()) == 0
 
 
 def test_routing_error_flags(api):
@@ -240,12 +275,12 @@ def run_rank(api, oracle, x, w13, w2, tw, ps, g, spr, k, tol, rows=None):
     ref_y = oracle.ffn(x, ref_pm["perm_pair"], ref_pm["group_offsets"], k, w13, w2, rows=rows)
     got_y = host_f64(y)[:n] if rows is None else host_f64(y)[np.asarray(rows)]
     if n:
-        assert rel_err(got_y, ref_y) <= tol, f"y_perm rank {g}: {rel_err(got_y, ref_y)}"
+        check_close(got_y, ref_y, tol, f"y_perm rank {g}")
     if rows is None:
         ref_out = oracle.unpermute(ref_y, ref_pm["pair_row"], tw)
         got_out = host_f64(out)
         if n:
-            assert rel_err(got_out, ref_out) <= tol, f"out rank {g}: {rel_err(got_out, ref_out)}"
+            check_close(got_out, ref_out, tol, f"out rank {g}")
         assert (got_out[(ref_pm["pair_row"] < 0).all(axis=1)] == 0).all()
         return got_out, ref_out
     return None, None
@@ -334,11 +369,12 @@ def test_padded_weight_rows(api, oracle, dtype, H, I, tol):
 
 
 def test_wide_and_stream_tiles_large_shape(api, oracle):
-    """H*I large enough that groups above 32 rows take the wide tiles: a several-tile group with a
-    wide and one with a narrow remainder, one-tile wide groups, narrow groups, an empty slot; every
-    row is compared."""
-    H, I, k, T = 4096, 2048, 4, 256
-    sizes = [300, 40, 0, 20, 128, 33, 1, 129 + 128, 32]
+    """H*I large enough that groups above 32 rows leave the stream path: one-tile groups of every
+    wide variant (33..64, 65..96 and 97..128 rows: 40, 33, 80, 96, 120, 128), groups of several tiles with
+    remainders in each of those classes and a narrow one (300, 257, 208, 352, 248, 460, 600), narrow groups,
+    an empty slot; every row is compared."""
+    H, I, k, T = 4096, 2048, 4, 1024
+    sizes = [300, 40, 0, 20, 128, 33, 1, 129 + 128, 32, 80, 96, 120, 128 + 80, 2 * 128 + 96, 128 + 120, 460, 600]
     spr = len(sizes)
     rng = np.random.default_rng(5)
     pairs = rng.permutation(T * k)[:sum(sizes)]
@@ -453,12 +489,14 @@ def test_malformed_lists_stay_in_bounds(api, dtype, H, I):
     assert valid[0] == 2 and np.array_equal(host_f64(out_buf[:T])[:, 0], valid.astype(np.float64))
 
 
-@pytest.mark.parametrize("w,routing", [(W.QWEN3_30B, "metro"), (W.QWEN3_235B, "metro"), (W.DSV3, "metro"),
-                                       (W.DSV3, "token_balanced")], ids=lambda v: getattr(v, "name", v))
-def test_full_size_sampled_rows(api, oracle, w, routing):
-    """Full shapes in the launch configuration the benchmark times: the busiest rank under the given
-    routing, weights drawn on the device; the oracle recomputes sampled rows (first/last row of the
-    widest group, of a one-tile group, and random rows) from host copies of the same bytes."""
+@pytest.mark.parametrize("w,routing", [(W.QWEN3_30B, "metro"), (W.QWEN3_30B, "token_balanced"),
+                                       (W.QWEN3_235B, "metro"), (W.QWEN3_235B, "token_balanced"),
+                                       (W.DSV3, "metro"), (W.DSV3, "token_balanced")],
+                         ids=lambda v: getattr(v, "name", v))
+def test_full_size_every_row(api, oracle, w, routing):
+    """Full shapes in the launch configuration the benchmark times (padded weight rows, the busiest rank under
+    the given routing, weights drawn on the device): EVERY row of y_perm and the whole combined output are
+    compared with the oracle, which works from host copies of the same bytes."""
     import torch
 
     _, s2e, ids = W.routing_inputs(w)
@@ -469,7 +507,6 @@ def test_full_size_sampled_rows(api, oracle, w, routing):
     ref = route_ref(ids, s2e, w.N, w.G, w.spr)
     assert np.array_equal(ps, ref["pair_slot"])
     g = int(np.argmax(np.bincount(ps.reshape(-1) // w.spr, minlength=w.G)))
-    print(f"full size {w.name}: rank {g}", flush=True)
     lw13, lw2 = W.device_expert_weights(w, "cuda")
     w13 = W.device_rank_share(lw13, s2e, g, w.spr, pad=True)       # the layout bench.py times
     w2 = W.device_rank_share(lw2, s2e, g, w.spr, pad=True)
@@ -480,32 +517,45 @@ def test_full_size_sampled_rows(api, oracle, w, routing):
     y = ffn_call(api, x, pm["perm_pair"], pm["group_offsets"], w.k, w13, w2)
     res = api.moe_unpermute(y, pm["pair_row"], dev_fp(tw))
     torch.cuda.synchronize()
-    assert not torch.isnan(y[:int(pm["n_pairs"].item())]).any(), "a row of the rank was not computed"
     ref_pm = oracle.permute(ps, g, w.spr)
     go = ref_pm["group_offsets"]
-    assert np.array_equal(pm["group_offsets"].cpu().numpy(), go)
     n = ref_pm["n_pairs"]
-    sizes = np.diff(go)
-    widest = int(np.argmax(sizes))
-    small = int(np.argmin(np.where(sizes > 0, sizes, 1 << 30)))
-    rng = np.random.default_rng(1)
-    rows = sorted({int(go[widest]), int(go[widest + 1] - 1), int(go[small]), int(go[small + 1] - 1), 0, n - 1,
-                   *rng.integers(0, n, size=10).tolist()})
+    print(f"full size {w.name} {routing}: rank {g}, {n} rows, groups {sorted(np.diff(go).tolist(), reverse=True)[:6]}",
+          flush=True)
+    assert np.array_equal(pm["group_offsets"].cpu().numpy(), go)
+    assert np.array_equal(pm["pair_row"].cpu().numpy(), ref_pm["pair_row"])
+    assert not torch.isnan(y[:n]).any(), "a row of the rank was not computed"
     host = lambda t: t.contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
-    ref_y = oracle.ffn(host(x), ref_pm["perm_pair"], go, w.k, host(w13), host(w2), rows=rows)
-    got_y = host_f64(y[torch.as_tensor(rows, device="cuda")])
-    assert rel_err(got_y, ref_y) <= BF16_TOL, rel_err(got_y, ref_y)
-    # combine: tokens whose pairs on this rank were all sampled can be checked exactly
-    pr = ref_pm["pair_row"]
-    row_pos = {r: i for i, r in enumerate(rows)}
-    checked = 0
-    for t in range(w.T):
-        mine = [(j, pr[t, j]) for j in range(w.k) if pr[t, j] >= 0]
-        if mine and all(r in row_pos for _, r in mine):
-            want = sum(float(tw[t, j]) * ref_y[row_pos[r]] for j, r in mine)
-            assert rel_err(host_f64(res[t]), want) <= BF16_TOL
-            checked += 1
-    assert checked > 0
-    # property that holds at any size: rows of tokens with no pair on this rank are zero
-    none = torch.as_tensor((pr < 0).all(axis=1), device="cuda")
-    assert (res[none] == 0).all()
+    ref_y = oracle.ffn(host(x), ref_pm["perm_pair"], go, w.k, host(w13), host(w2))
+    check_close(host_f64(y[:n]), ref_y, BF16_TOL, f"{w.name} {routing} y_perm")
+    ref_out = oracle.unpermute(ref_y, ref_pm["pair_row"], tw)
+    got_out = host_f64(res)
+    check_close(got_out, ref_out, BF16_TOL, f"{w.name} {routing} out")
+    # rows of tokens with no pair on this rank are exactly zero
+    assert (got_out[(ref_pm["pair_row"] < 0).all(axis=1)] == 0).all()
+
+
+def test_nan_rows_stay_nan(api):
+    """A NaN activation makes every output of its rows NaN -- never Inf or a finite number (rounding a NaN
+    to bf16 by adding the rounding bias to its bits could carry it into the exponent) -- and leaves the other
+    tokens' rows finite."""
+    import torch
+
+    T, k, spr, H, I = 64, 2, 4, 512, 256
+    rng = np.random.default_rng(11)
+    ps = rng.integers(0, spr, size=(T, k)).astype(np.int32)
+    x = dev_fp(W.activations(T, H, 21, "bf16")).clone()
+    xb = x.view(torch.int16)
+    xb[5, 7] = 0x7F81                       # signalling NaN with only low mantissa bits set
+    xb[9, :] = -1                           # 0xFFFF: every mantissa bit set, sign set
+    w13, w2 = (dev_fp(a) for a in W.expert_weights(spr, H, I, 22, "bf16"))
+    pm = api.moe_permute(dev_i32(ps), 0, spr)
+    y = ffn_call(api, x, pm["perm_pair"], pm["group_offsets"], k, w13, w2)
+    out = api.moe_unpermute(y, pm["pair_row"], torch.full((T, k), 0.5, device="cuda"))
+    torch.cuda.synchronize()
+    bad = torch.zeros(T, dtype=torch.bool, device="cuda")
+    bad[5] = bad[9] = True
+    assert torch.isnan(out[bad]).all()
+    assert torch.isfinite(out[~bad]).all()
+    rows = pm["pair_row"][bad].reshape(-1).long()
+    assert torch.isnan(y[rows]).all()

@@ -112,6 +112,37 @@ def test_random_ffn_and_combine(api, oracle):
         assert np.abs(out.float().cpu().numpy() - want).max() / max(np.abs(want).max(), 1e-30) <= tol, what
 
 
+@pytest.mark.parametrize("seed", [31, 32, 33])
+def test_random_ffn_large_shape(api, oracle, seed):
+    """Random group sizes at a shape large enough (H*I >= 4096*2048) for every tile class of the bandwidth-bound
+    regime: narrow, one-tile wide and several-tile groups, with one group that may hold most of the rows."""
+    import torch
+
+    rng = np.random.default_rng(seed)
+    H, I = 4096, 2048
+    spr, k, T = int(rng.integers(3, 7)), int(rng.integers(2, 5)), int(rng.choice([200, 450, 700]))
+    probs = rng.dirichlet(np.full(spr, 0.4))
+    ps = rng.choice(spr, size=(T, k), p=probs).astype(np.int32)
+    ps[rng.random((T, k)) < 0.1] = -1
+    x = W.activations(T, H, 600 + seed, "bf16")
+    w13, w2 = W.expert_weights(spr, H, I, 700 + seed, "bf16")
+    tw = W.gating_weights(T, k, 800 + seed)
+    pm = api.moe_permute(dev_i(ps), 0, spr)
+    rp = oracle.permute(ps, 0, spr)
+    n = rp["n_pairs"]
+    what = f"seed {seed}: spr={spr} k={k} T={T} groups {np.diff(rp['group_offsets']).tolist()}"
+    print(what, flush=True)
+    y = torch.full((T * k, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    api.moe_grouped_ffn(dev_fp(x), pm["perm_pair"], pm["group_offsets"], k, dev_fp(w13), dev_fp(w2), y_perm=y)
+    out = api.moe_unpermute(y, pm["pair_row"], torch.from_numpy(tw).cuda())
+    ref = oracle.ffn(x, rp["perm_pair"], rp["group_offsets"], k, w13, w2)
+    got = y[:n].float().cpu().numpy().astype(np.float64)
+    row_err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    assert row_err.max() <= 2e-2, f"{what}: row {int(row_err.argmax())} off by {row_err.max()}"
+    want = oracle.unpermute(ref, rp["pair_row"], tw)
+    assert np.abs(out.float().cpu().numpy() - want).max() / np.abs(want).max() <= 1e-2, what
+
+
 def test_random_gate_topk(api, oracle):
     rng = np.random.default_rng(24)
     for it in range(30):
