@@ -403,6 +403,7 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 extern "C" size_t moe_gate_topk_workspace_bytes(int T, int H, int N, int dtype) {
     using namespace metro;
     if (T < 0 || H < 1 || N < 1) return 0;
+    if (T == 0) return 256;                                       // an empty batch has no partial sums
     return align256((size_t)gate_chunks(T, H, N, dtype) * T * N * sizeof(float)) + 256;
 }
 
