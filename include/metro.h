@@ -34,6 +34,7 @@ extern "C" {
 #define METRO_ERR_UNSUPPORTED (-2)   /* a size beyond the limits above, unknown dtype */
 #define METRO_ERR_WORKSPACE (-3)     /* workspace smaller than the *_workspace_bytes() figure */
 #define METRO_ERR_HIP (-4)           /* the HIP runtime refused a launch */
+#define METRO_ERR_TOO_LARGE (-5)     /* the problem needs more than the library's built-in scratch buffer */
 
 /* bits of err_flag[layer] */
 #define METRO_FLAG_BAD_ID 1          /* a top-k id outside [-1, N) */
@@ -162,6 +163,25 @@ int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, const int32
                             size_t ws_bytes, void* stream);
 int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, int spr, int H, int I, int dtype,
                          const void* w2, int ldw2, void* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * moe_grouped_ffn_static_ws -- moe_grouped_ffn for callers that cannot allocate or size a workspace (code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc): the intermediate activations
+ * live in an array built into the library, METRO_STATIC_WS_BYTES per GPU, held from library load until the
+ * process ends.  Same arguments and results as moe_grouped_ffn without ws / ws_bytes; same kernels.
+ *   - A problem whose moe_grouped_ffn_workspace_bytes() exceeds moe_grouped_ffn_static_ws_bytes()
+ *     (bf16: T*k*I*2 + 256 bytes; the DeepSeek-V3-shaped decode batch T*k = 8192, I = 2048 just fits)
+ *     is refused with METRO_ERR_TOO_LARGE and nothing is enqueued.
+ *   - The call allocates nothing.  Its first use on a device looks up the array's address.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *     different threads) race on it; serialise them or use moe_grouped_ffn with separate workspaces.
+ *     Nothing in the array has to be cleared between calls.
+ */
+#define METRO_STATIC_WS_BYTES ((size_t)(32u << 20) + 256u)
+size_t moe_grouped_ffn_static_ws_bytes(void);
+int moe_grouped_ffn_static_ws(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T, int k,
+                              int spr, int H, int I, int dtype, const void* w13, int ldw13, const void* w2,
+                              int ldw2, void* y_perm, void* stream);
 
 /*
  * moe_unpermute -- the rank's share of the combine step (Sec. 2.2): for every token,

@@ -16,13 +16,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmetro.so")
 _lib = None
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
 FLAG_BAD_ID, FLAG_NO_REPLICA, FLAG_BAD_PLACEMENT = 1, 2, 4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ("metro_status_string", "metro_route", "metro_route_token_balanced", "moe_permute",
            "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gate_up",
-           "moe_grouped_ffn_down", "moe_unpermute", "moe_gate_topk_workspace_bytes", "moe_gate_topk")
+           "moe_grouped_ffn_down", "moe_unpermute", "moe_gate_topk_workspace_bytes", "moe_gate_topk",
+           "moe_grouped_ffn_static_ws_bytes", "moe_grouped_ffn_static_ws")
 
 
 class MetroError(RuntimeError):
@@ -56,6 +57,10 @@ def load() -> ctypes.CDLL:
         lib.moe_grouped_ffn_gate_up.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, sz, vp]
         lib.moe_grouped_ffn_down.restype = ci
         lib.moe_grouped_ffn_down.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, sz, vp]
+        lib.moe_grouped_ffn_static_ws_bytes.restype = sz
+        lib.moe_grouped_ffn_static_ws_bytes.argtypes = []
+        lib.moe_grouped_ffn_static_ws.restype = ci
+        lib.moe_grouped_ffn_static_ws.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, vp, ci, vp, vp]
         lib.moe_unpermute.restype = ci
         lib.moe_unpermute.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
         lib.moe_gate_topk_workspace_bytes.restype = sz
@@ -195,6 +200,25 @@ def moe_grouped_ffn(x: torch.Tensor, perm_pair: torch.Tensor, group_offsets: tor
                                   _dev(group_offsets, torch.int32, "group_offsets"), T, k, spr, H, I, code,
                                   p13, ld13, p2, ld2, _dev(y_perm, x.dtype, "y_perm"),
                                   _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+    return y_perm
+
+
+def moe_grouped_ffn_static_ws(x: torch.Tensor, perm_pair: torch.Tensor, group_offsets: torch.Tensor, k: int,
+                              w13: torch.Tensor, w2: torch.Tensor, y_perm: torch.Tensor) -> torch.Tensor:
+    """moe_grouped_ffn on the library's built-in workspace: the caller passes inputs and the output only."""
+    T, H = x.shape
+    spr, two_i, _ = w13.shape
+    I = two_i // 2
+    if tuple(w13.shape) != (spr, 2 * I, H) or tuple(w2.shape) != (spr, H, I):
+        raise ValueError("weight shapes must be w13 [spr,2I,H] and w2 [spr,H,I]")
+    if perm_pair.numel() < T * k or group_offsets.numel() != spr + 1 or tuple(y_perm.shape) != (T * k, H):
+        raise ValueError("perm_pair must hold T*k entries, group_offsets spr+1, y_perm [T*k,H]")
+    p13, ld13 = _weights(w13, x.dtype, "w13")
+    p2, ld2 = _weights(w2, x.dtype, "w2")
+    _check(load().moe_grouped_ffn_static_ws(_dev(x, x.dtype, "x"), _dev(perm_pair, torch.int32, "perm_pair"),
+                                            _dev(group_offsets, torch.int32, "group_offsets"), T, k, spr, H, I,
+                                            _dtype_code(x), p13, ld13, p2, ld2, _dev(y_perm, x.dtype, "y_perm"),
+                                            _stream()))
     return y_perm
 
 

@@ -494,6 +494,27 @@ inline int tile_rows_for(int H, int I) { return (size_t)H * I < (size_t)2048 * 1
 
 inline int launched() { return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP; }
 
+// Built-in workspace of moe_grouped_ffn_static_ws: one array per GPU, held from the moment the library is
+// loaded on that GPU until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it yields (one per device) is what kernels and copies get.
+constexpr size_t kStaticWsBytes = METRO_STATIC_WS_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_ws(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> table[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return METRO_ERR_HIP;
+    void* p = table[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return METRO_ERR_HIP;
+        table[dev].store(p, std::memory_order_release);      // a racing first call stores the same address
+    }
+    *out = p;
+    return METRO_OK;
+}
+
 }  // namespace
 }  // namespace metro
 
@@ -611,4 +632,23 @@ extern "C" int moe_grouped_ffn(const void* x, const int32_t* perm_pair, const in
     if (rc == METRO_OK)
         rc = moe_grouped_ffn_down(group_offsets, T, k, spr, H, I, dtype, w2, ldw2, y_perm, ws, ws_bytes, stream);
     return rc;
+}
+
+extern "C" size_t moe_grouped_ffn_static_ws_bytes(void) { return metro::kStaticWsBytes; }
+
+extern "C" int moe_grouped_ffn_static_ws(const void* x, const int32_t* perm_pair, const int32_t* group_offsets, int T,
+                                         int k, int spr, int H, int I, int dtype, const void* w13, int ldw13,
+                                         const void* w2, int ldw2, void* y_perm, void* stream) {
+    using namespace metro;
+    if (T < 0 || k < 1 || spr < 1 || H < 1 || I < 1) return METRO_ERR_INVALID_ARG;
+    if (dtype != METRO_DTYPE_BF16 && dtype != METRO_DTYPE_F32) return METRO_ERR_UNSUPPORTED;
+    if (spr > kMaxSpr || (int64_t)T * k >= (1 << 24)) return METRO_ERR_UNSUPPORTED;
+    if (moe_grouped_ffn_workspace_bytes(T, k, spr, H, I, dtype) > kStaticWsBytes) return METRO_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    const int rc = static_ws(&ws);
+    if (rc != METRO_OK) return rc;
+    // the intermediate activations of rows < n_pairs are written by the first stage before the second reads
+    // them, so nothing in the array has to start at zero
+    return moe_grouped_ffn(x, perm_pair, group_offsets, T, k, spr, H, I, dtype, w13, ldw13, w2, ldw2, y_perm, ws,
+                           kStaticWsBytes, stream);
 }

@@ -133,6 +133,7 @@ extern "C" const char* metro_status_string(int status) {
         case METRO_ERR_UNSUPPORTED: return "size or dtype beyond the supported limits";
         case METRO_ERR_WORKSPACE: return "workspace too small";
         case METRO_ERR_HIP: return "HIP launch failed";
+        case METRO_ERR_TOO_LARGE: return "problem larger than the library's built-in scratch buffer";
         default: return "unknown status";
     }
 }

@@ -43,7 +43,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     assert lib.metro_status_string(0) == b"ok"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert lib.metro_status_string(code) not in (b"ok", b"unknown status")
     assert lib.metro_status_string(-99) == b"unknown status"
 
@@ -78,6 +78,23 @@ def test_host_side_argument_checks(lib):
     assert lib.moe_gate_topk(one, None, 256, 32, 256, 64, 8, 1, one, one, None, one, gate_ws, None) == -1    # null
     assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 8, 1, one, one, None, one, gate_ws - 1, None) == -3
     assert lib.moe_gate_topk(None, None, 256, 0, 256, 64, 8, 1, None, None, None, None, 0, None) == 0        # empty batch
+
+
+def test_size_queries_take_every_batch_size(lib):
+    """The workspace queries are plain host arithmetic: an empty batch and bad sizes must not trap."""
+    assert lib.moe_gate_topk_workspace_bytes(0, 256, 64, 1) >= 0
+    assert lib.moe_gate_topk_workspace_bytes(0, 7168, 256, 1) >= 0
+    assert lib.moe_gate_topk_workspace_bytes(-1, 256, 64, 1) == 0
+    assert lib.moe_grouped_ffn_workspace_bytes(0, 2, 3, 256, 128, 1) >= 0
+    assert lib.moe_grouped_ffn_workspace_bytes(4, 0, 3, 256, 128, 1) == 0
+    cap = lib.moe_grouped_ffn_static_ws_bytes()
+    assert cap >= lib.moe_grouped_ffn_workspace_bytes(1024, 8, 36, 7168, 2048, 1)     # the headline shape fits
+    one = ctypes.c_void_p(256)
+    # one row more than fits: refused on the host, before anything touches the device
+    assert lib.moe_grouped_ffn_workspace_bytes(1025, 8, 36, 7168, 2048, 1) > cap
+    assert lib.moe_grouped_ffn_static_ws(one, one, one, 1025, 8, 36, 7168, 2048, 1, one, 7168, one, 2048, one,
+                                         None) == -5
+    assert lib.moe_grouped_ffn_static_ws(one, one, one, 4, 2, 65, 256, 128, 1, one, 256, one, 128, one, None) == -2
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):
