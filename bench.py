@@ -10,6 +10,10 @@ rank, T=1024, Zipf s=1.0, H=7168, I=2048, bf16) -- the shape the HBM-roofline ta
 Prints ONE JSON line: `value` = achieved algorithmic HBM GB/s of the slowest rank's expert FFN under
 METRO routing; the route latency, FFN times under both routers, the roofline of the dominant kernel
 (gate/up) and the CPU-oracle baseline ride along in the same object.
+
+METRO and token-balanced routing are compared inside one timed loop that alternates a METRO step and a
+token-balanced step (each on its own slowest rank), so that clock and power drift hit both sides alike; the
+same comparison at the two Qwen3-shaped configs rides along in `per_config`.
 """
 from __future__ import annotations
 
@@ -87,11 +91,14 @@ class HotPath:
         api.moe_unpermute(self.y, self.pb["pair_row"], self.tw, out=self.out)
         m(5)
 
-    def graph_ms_per_step(self, g: int, replays: int = 20) -> float:
-        """The same step replayed from a HIP graph (one step per weight copy captured, so the rotation
-        is kept): what a serving loop that captures the layer would see; no events inside."""
+    def graph_ms_per_step(self, g: int, replays: int = 10) -> float:
+        """The same step replayed from a HIP graph: what a serving loop that captures the layer would see; no
+        events inside.  At least eight steps are captured per graph (a multiple of the weight copies, so the
+        rotation is kept): one graph launch costs tens of microseconds that back-to-back eager launches hide,
+        and a graph holding a single 0.7 ms step would charge all of it to that step."""
         torch = self.torch
         n = len(self.copies[g])
+        n = n * max(1, -(-8 // n))
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         self.step(g)
@@ -123,37 +130,51 @@ class HotPath:
             tot += ev[2].elapsed_time(ev[4])
         return 1e3 * tot / iters
 
-    def timed(self, g: int, steps: int, warmup: int):
-        """W untimed + K timed steps; returns (ms_per_step, per-stage mean us).
-
-        Inside the timed region only the two FFN kernels are bracketed by events (an event costs a few
-        microseconds of stream time, which matters next to the short stages); the other stages'
-        durations come from a second, untimed pass that brackets every stage."""
+    def stage_breakdown(self, g: int, n: int = 20):
+        """Mean duration of every stage from a pass that brackets each stage with events (not part of the
+        timed steps: an event costs a few microseconds of stream time, which matters next to the short stages)."""
         torch = self.torch
-        ev = lambda: torch.cuda.Event(enable_timing=True)
-        for _ in range(warmup):
-            self.step(g)
-        evs = [[None, None, ev(), ev(), ev(), None] for _ in range(steps)]
-        evs[0][0], evs[-1][5] = ev(), ev()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for s in range(steps):
-            self.step(g, evs[s])
-        torch.cuda.synchronize()
-        wall_ms = 1e3 * (time.perf_counter() - t0)
-        dev_ms = evs[0][0].elapsed_time(evs[-1][5])
-        per_step = {n: np.array([1e3 * e[i].elapsed_time(e[i + 1]) for e in evs]) for i, n in ((2, "gate_up"), (3, "down"))}
-        stage = {n: float(v.mean()) for n, v in per_step.items()}
-        ffn = per_step["gate_up"] + per_step["down"]
-        self.ffn_quantiles = [round(float(np.percentile(ffn, q)), 1) for q in (10, 50, 90)]
-        full = [[ev() for _ in range(6)] for _ in range(min(steps, 20))]
+        full = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n)]
         for e in full:
             self.step(g, e)
         torch.cuda.synchronize()
-        for i, n in enumerate(self.STAGES):
-            if n not in stage:
-                stage[n] = 1e3 * float(np.mean([e[i].elapsed_time(e[i + 1]) for e in full]))
-        return max(wall_ms, dev_ms) / steps, {n: stage[n] for n in self.STAGES}
+        return {name: 1e3 * float(np.mean([e[i].elapsed_time(e[i + 1]) for e in full]))
+                for i, name in enumerate(self.STAGES)}
+
+
+def interleaved(torch, sides, steps: int, warmup: int):
+    """W untimed + K timed iterations; an iteration runs one step of every side in turn (METRO step, then
+    token-balanced step), so whatever drifts during the run drifts for both.  One event separates consecutive
+    steps and three bracket the two FFN kernels of each step.  Returns per side: ms per step (device time between
+    its boundary events), wall-clock ms of the whole loop, and the per-step FFN stage times in us."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for _ in range(warmup):
+        for hp, g in sides:
+            hp.step(g)
+    n = len(sides)
+    bound = [ev() for _ in range(steps * n + 1)]
+    inner = [[(ev(), ev(), ev()) for _ in range(steps)] for _ in sides]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    bound[0].record()
+    for s in range(steps):
+        for i, (hp, g) in enumerate(sides):
+            a, b, c = inner[i][s]
+            hp.step(g, [None, None, a, b, c, bound[s * n + i + 1]])
+    torch.cuda.synchronize()
+    wall_ms = 1e3 * (time.perf_counter() - t0)
+    out = []
+    for i in range(n):
+        step_ms = np.array([bound[s * n + i].elapsed_time(bound[s * n + i + 1]) for s in range(steps)])
+        gu = np.array([1e3 * a.elapsed_time(b) for a, b, _ in inner[i]])
+        dn = np.array([1e3 * b.elapsed_time(c) for _, b, c in inner[i]])
+        out.append(dict(ms_per_step=float(step_ms.mean()), gate_up_us=gu, down_us=dn))
+    dev_ms = bound[0].elapsed_time(bound[-1])
+    # the driver's clock sees the whole loop: never report a step shorter than its share of the wall clock
+    scale = max(1.0, wall_ms / dev_ms)
+    for o in out:
+        o["ms_per_step"] *= scale
+    return out, wall_ms
 
 
 def graph_replay_us(torch, launch, reps: int = 20, replays: int = 10) -> float:
@@ -288,44 +309,100 @@ def cpu_baseline(oracle, W, w, ids, s2e, host_x, host_w13, host_w2, perm, ffn_by
                 ffn_us_extrapolated=round(1e6 * full_s, 1), route_us_per_batch=round(route_us, 2))
 
 
+def quantiles(v):
+    return [round(float(np.percentile(v, q)), 1) for q in (10, 50, 90)]
+
+
+def compare_routings(api, torch, W, w, steps: int, warmup: int, routings=("metro", "token_balanced"), lw=None,
+                     ranks=None, pad: bool = True, stages: bool = False):
+    """One workload under the given routings: each side's slowest rank is found with all G shares resident, then
+    the sides are timed in one interleaved loop.  Returns {routing: result dict} and the objects the caller may
+    still need (inputs, the sides' HotPath objects)."""
+    _, s2e, ids = W.routing_inputs(w)
+    d_ids = torch.from_numpy(ids).cuda().unsqueeze(0)
+    d_s2e = torch.from_numpy(s2e).cuda().unsqueeze(0)
+    x = W.device_activations(w, "cuda")
+    tw = torch.from_numpy(W.gating_weights(w.T, w.k, w.seed(0, 4))).cuda()
+    lw13, lw2 = lw if lw is not None else W.device_expert_weights(w, "cuda")
+    ranks = list(range(w.G)) if ranks is None else list(ranks)
+    shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr, pad=pad), W.device_rank_share(lw2, s2e, g, w.spr, pad=pad))
+              for g in ranks}
+    del lw13, lw2
+    sides, per_rank = [], {}
+    for routing in routings:
+        hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
+        per_rank[routing] = {g: hp.ffn_only_us(g) for g in ranks}
+        g = max(per_rank[routing], key=per_rank[routing].get)
+        hp.copies = {g: hp.copies[g]}
+        sides.append((hp, g))
+    keep = {g for _, g in sides}
+    for g in list(shares):
+        if g not in keep:
+            del shares[g]
+    torch.cuda.empty_cache()
+    timed, wall_ms = interleaved(torch, sides, steps, warmup)
+    out = {}
+    for routing, (hp, g), t in zip(routings, sides, timed):
+        assert int(hp.rb["err_flag"].item()) == 0
+        active = int(hp.rb["rank_active"][0, g].item())
+        P = int(hp.pb["n_pairs"].item())
+        gu_b, dn_b = algorithmic_bytes(active, P, w.H, w.I)
+        ffn = t["gate_up_us"] + t["down_us"]
+        out[routing] = dict(rank=g, ms_per_step=t["ms_per_step"], ffn_q=quantiles(ffn), ffn_us=float(ffn.mean()),
+                            gate_up_us=float(t["gate_up_us"].mean()), down_us=float(t["down_us"].mean()),
+                            active=active, pairs=P, bytes=(gu_b, dn_b), lam=int(hp.rb["rank_active"].max().item()),
+                            per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank[routing].items()},
+                            stage_us=({k: round(v, 2) for k, v in hp.stage_breakdown(g).items()} if stages else None))
+    return out, dict(ids=ids, s2e=s2e, x=x, tw=tw, d_ids=d_ids, d_s2e=d_s2e, shares=shares, sides=dict(zip(routings, sides)),
+                     wall_ms=wall_ms)
+
+
+def ratio_of(res):
+    """METRO over token-balanced FFN time (medians); worth stating only when the gap exceeds both sides' spread."""
+    me, tb = res["metro"], res["token_balanced"]
+    gap = abs(me["ffn_q"][1] - tb["ffn_q"][1])
+    spread = max(me["ffn_q"][2] - me["ffn_q"][0], tb["ffn_q"][2] - tb["ffn_q"][0])
+    return {"ffn_time_ratio": round(me["ffn_q"][1] / tb["ffn_q"][1], 3), "conclusive": bool(gap > spread),
+            "measured": "interleaved steps in one loop"}
+
+
+def config_summary(w, res):
+    """The comparison at one workload, as it goes into the JSON line."""
+    d = {"T": w.T, "H": w.H, "I": w.I, "slots_per_rank": w.spr, "metro_vs_token_balanced": ratio_of(res)}
+    for routing, r in res.items():
+        gu_b, dn_b = r["bytes"]
+        d[routing] = {"rank": r["rank"], "activated": r["active"], "pairs": r["pairs"], "max_activated_per_rank": r["lam"],
+                      "ffn_us_p10_p50_p90": r["ffn_q"], "ms_per_step": round(r["ms_per_step"], 4),
+                      "gate_up": {"us": round(r["gate_up_us"], 1), "algorithmic_gbs": round(gu_b / r["gate_up_us"] / 1e3, 1),
+                                  "frac_of_hbm_peak": round(gu_b / r["gate_up_us"] / 1e3 / HBM_PEAK_GBS, 4)},
+                      "down": {"us": round(r["down_us"], 1), "algorithmic_gbs": round(dn_b / r["down_us"] / 1e3, 1),
+                               "frac_of_hbm_peak": round(dn_b / r["down_us"] / 1e3 / HBM_PEAK_GBS, 4)},
+                      "ffn_algorithmic_gbs": round((gu_b + dn_b) / r["ffn_us"] / 1e3, 1)}
+    return d
+
+
 def replication_sweep(api, torch, W, steps: int, warmup: int):
     """The paper's main axis (Sec. 6.2, Fig. 10): replication ratio 1.0x .. 1.5x at the three FFN
     shapes, at the config's batch and at the 32-tokens-per-rank decode batch.  Per cell and router:
     max activated experts per rank, pairs on the slowest rank, its FFN time (gate/up + down events)."""
     rows = []
     for base in (W.QWEN3_30B, W.QWEN3_235B, W.DSV3):
-        lw13, lw2 = W.device_expert_weights(base, "cuda")
+        lw = W.device_expert_weights(base, "cuda")
         for ratio in (1.0, 1.125, 1.25, 1.5):
             spr = int(round(base.N * ratio / base.G))
             for T in sorted({32 * base.G, base.T}):
                 w = base.with_(spr=spr, T=T)
-                _, s2e, ids = W.routing_inputs(w)
-                d_ids = torch.from_numpy(ids).cuda().unsqueeze(0)
-                d_s2e = torch.from_numpy(s2e).cuda().unsqueeze(0)
-                x = W.device_activations(w, "cuda")
-                tw = torch.from_numpy(W.gating_weights(w.T, w.k, w.seed(0, 4))).cuda()
-                shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr, pad=True),
-                              W.device_rank_share(lw2, s2e, g, w.spr, pad=True)) for g in range(w.G)}
+                res, keep = compare_routings(api, torch, W, w, steps, warmup, lw=lw)
                 cell = dict(workload=base.name, replication=ratio, slots_per_rank=spr, T=T)
-                for routing in ("metro", "token_balanced"):
-                    hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
-                    per_rank = {g: hp.ffn_only_us(g) for g in range(w.G)}
-                    g = max(per_rank, key=per_rank.get)
-                    hp.copies = {g: hp.copies[g]}
-                    _, stage = hp.timed(g, steps, warmup)
-                    assert int(hp.rb["err_flag"].item()) == 0
-                    cell[routing] = dict(max_activated=int(hp.rb["rank_active"].max().item()), slowest_rank=g,
-                                         activated=int(hp.rb["rank_active"][0, g].item()),
-                                         pairs=int(hp.pb["n_pairs"].item()),
-                                         ffn_us=round(stage["gate_up"] + stage["down"], 1))
-                    del hp
-                cell["ffn_time_metro_over_token_balanced"] = round(
-                    cell["metro"]["ffn_us"] / cell["token_balanced"]["ffn_us"], 3)
+                for routing, r in res.items():
+                    cell[routing] = dict(max_activated=r["lam"], slowest_rank=r["rank"], activated=r["active"],
+                                         pairs=r["pairs"], ffn_us=round(r["ffn_us"], 1), ffn_us_p10_p50_p90=r["ffn_q"])
+                cell["ffn_time_metro_over_token_balanced"] = ratio_of(res)["ffn_time_ratio"]
                 rows.append(cell)
                 print(json.dumps(cell), file=sys.stderr, flush=True)
-                del shares, x
+                del keep, res
                 torch.cuda.empty_cache()
-        del lw13, lw2
+        del lw
         torch.cuda.empty_cache()
     return rows
 
@@ -339,6 +416,32 @@ def optional(fn, *a, **kw):
         return {"error": repr(e)}
 
 
+def ffn_source_sha16() -> str:
+    """Identifies the FFN kernel build a byte-counter profile belongs to: a hash of the kernel sources (the GPU machine
+    has no git history to ask)."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in ("ffn.hip", "device_utils.h", "host_utils.h"):
+        with open(os.path.join(ROOT, "paper_2512_09277_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload: str, routing: str, rank: int):
+    """HBM-side bytes per launch of the two FFN kernels from the committed rocprofv3 counter summary
+    (profiles/ffn_traffic_<workload>.json, written by paper_2512_09277_amd/rocprof_summary.py), or None with the
+    reason when that summary was taken on another rank, routing or kernel source than this run's."""
+    path = os.path.join(ROOT, "profiles", f"ffn_traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None, "no counter summary for this workload"
+    rec = json.load(open(path))
+    for key, have in (("routing", routing), ("rank", rank), ("ffn_source_sha16", ffn_source_sha16())):
+        if rec.get(key) != have:
+            return None, f"counter summary is for {key}={rec.get(key)!r}, this run has {have!r}"
+    return rec, None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -346,7 +449,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="deepseek_v3_decode")
     ap.add_argument("--rank", type=int, default=-1, help="pin the measured rank (skips the per-rank search)")
-    ap.add_argument("--only-metro", action="store_true", help="skip the token-balanced comparison and the sweep")
+    ap.add_argument("--only-metro", action="store_true",
+                    help="METRO routing only: no token-balanced comparison, no other configs, no sweep")
     ap.add_argument("--only-token-balanced", action="store_true",
                     help="run the path under token-balanced routing only and print a reduced line (for profiling "
                          "the baseline's rank with rocprofv3)")
@@ -358,6 +462,7 @@ def main() -> int:
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for rocprofv3 byte counters)")
     ap.add_argument("--no-hip-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the two Qwen3-shaped configs")
     ap.add_argument("--replication-sweep", action="store_true",
                     help="instead of the benchmark line: METRO vs token-balanced over replication ratios "
                          "1.0x..1.5x at the three FFN shapes (one JSON line of its own)")
@@ -386,19 +491,6 @@ def main() -> int:
         print("that workload has no FFN shape", file=sys.stderr)
         return 2
 
-    _, s2e, ids = W.routing_inputs(w)
-    d_ids = torch.from_numpy(ids).cuda().unsqueeze(0)
-    d_s2e = torch.from_numpy(s2e).cuda().unsqueeze(0)
-    x = W.device_activations(w, "cuda")
-    tw = torch.from_numpy(W.gating_weights(w.T, w.k, w.seed(0, 4))).cuda()
-    lw13, lw2 = W.device_expert_weights(w, "cuda")
-    ranks = range(w.G) if args.rank < 0 else [args.rank]
-    pad = not args.dense_weights
-    shares = {g: (W.device_rank_share(lw13, s2e, g, w.spr, pad=pad), W.device_rank_share(lw2, s2e, g, w.spr, pad=pad))
-              for g in ranks}
-    del lw13, lw2
-    torch.cuda.synchronize()
-
     if args.calibration_copy:
         src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -407,42 +499,33 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    result = {}
-    routings = ("token_balanced",) if args.only_token_balanced else ("metro",) if args.only_metro else ("metro", "token_balanced")
-    for routing in routings:
-        hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
-        per_rank = {g: hp.ffn_only_us(g) for g in ranks}
-        g = max(per_rank, key=per_rank.get)
-        hp.copies = {g: hp.copies[g]}
-        ms_per_step, stage = hp.timed(g, args.steps, args.warmup)
-        graph_ms = None if args.no_hip_graph else optional(hp.graph_ms_per_step, g)
-        route_graph_us = None if args.no_hip_graph else optional(
-            graph_replay_us, torch, lambda: hp.route_fn(d_ids, d_s2e, w.N, w.G, w.spr, out=hp.rb))
-        assert int(hp.rb["err_flag"].item()) == 0
-        active = int(hp.rb["rank_active"][0, g].item())
-        P = int(hp.pb["n_pairs"].item())
-        gu_b, dn_b = algorithmic_bytes(active, P, w.H, w.I)
-        ffn_us = stage["gate_up"] + stage["down"]
-        result[routing] = dict(rank=g, ms_per_step=ms_per_step, ffn_q=hp.ffn_quantiles, graph_ms=graph_ms, route_graph_us=route_graph_us, stage_us={k: round(v, 2) for k, v in stage.items()},
-                               ffn_us=ffn_us, active=active, pairs=P, bytes=(gu_b, dn_b),
-                               lam=int(hp.rb["rank_active"].max().item()),
-                               per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank.items()},
-                               perm={k: v.cpu().numpy() for k, v in hp.pb.items()})
+    routings = (("token_balanced",) if args.only_token_balanced else ("metro",) if args.only_metro
+                else ("metro", "token_balanced"))
+    ranks = None if args.rank < 0 else [args.rank]
+    result, keep = compare_routings(api, torch, W, w, args.steps, args.warmup, routings=routings, ranks=ranks,
+                                    pad=not args.dense_weights, stages=True)
+    d_ids, d_s2e, x = keep["d_ids"], keep["d_s2e"], keep["x"]
+    for routing, (hp, g) in keep["sides"].items():
+        r = result[routing]
+        r["graph_ms"] = None if args.no_hip_graph else optional(hp.graph_ms_per_step, g)
+        r["route_graph_us"] = None if args.no_hip_graph else optional(
+            graph_replay_us, torch, lambda hp=hp: hp.route_fn(d_ids, d_s2e, w.N, w.G, w.spr, out=hp.rb))
+        r["perm"] = {k: v.cpu().numpy() for k, v in hp.pb.items()}
     if args.only_token_balanced:
         tb = result["token_balanced"]
         print(json.dumps({"mode": "token_balanced_only", "workload": w.name, "steps": args.steps, "rank": tb["rank"],
                           "activated": tb["active"], "pairs": tb["pairs"], "stage_us": tb["stage_us"],
+                          "ffn_source_sha16": ffn_source_sha16(),
                           "algorithmic_bytes_per_launch": {"gate_up": tb["bytes"][0], "down": tb["bytes"][1]}}))
         return 0
     me = result["metro"]
     gu_b, dn_b = me["bytes"]
     ffn_gbs = (gu_b + dn_b) / (me["ffn_us"] * 1e-6) / 1e9
-    gu_gbs = gu_b / (me["stage_us"]["gate_up"] * 1e-6) / 1e9
-
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "ffn_gate_up_dsv3_traffic.json")
-    if os.path.exists(tpath) and w.name == "deepseek_v3_decode":
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    gu_gbs = gu_b / (me["gate_up_us"] * 1e-6) / 1e9
+    dn_gbs = dn_b / (me["down_us"] * 1e-6) / 1e9
+    rec, why = recorded_traffic(w.name, "metro", me["rank"])
+    shares = keep["shares"]
+    num = lambda v: round(v, 4) if isinstance(v, float) else v
 
     line = {
         "metric": METRIC, "value": round(ffn_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -450,56 +533,73 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "E": w.N, "top_k": w.k, "G_logical_ranks": w.G, "slots_per_rank": w.spr,
                    "T": w.T, "zipf_s": w.s, "H": w.H, "I": w.I, "measured_rank": me["rank"], "routing": "metro",
-                   "weight_row_pitch": {"w13": shares[me["rank"]][0].stride(1), "w2": shares[me["rank"]][1].stride(1)}},
+                   "weight_row_pitch": {"w13": shares[me["rank"]][0].stride(1), "w2": shares[me["rank"]][1].stride(1)},
+                   "timed_loop": "METRO step and token-balanced step alternate; ms_per_step is the METRO step"
+                   if "token_balanced" in result else "METRO steps only"},
         "route_us_per_batch": me["stage_us"]["route"],
-        "route_us_per_batch_graph_replay": {"metro": round(me["route_graph_us"], 2)
-                                            if isinstance(me["route_graph_us"], float) else me["route_graph_us"]},
+        "route_us_per_batch_graph_replay": {"metro": num(me["route_graph_us"])},
         "ffn_us": {"metro": round(me["ffn_us"], 1)},
         "ffn_us_p10_p50_p90": {"metro": me["ffn_q"]},
         "max_activated_per_rank": {"metro": me["lam"]},
         "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
         "stage_us": me["stage_us"],
-        "ms_per_step_hip_graph": {"metro": round(me["graph_ms"], 4) if isinstance(me["graph_ms"], float) else me["graph_ms"]},
+        "ms_per_step_hip_graph": {"metro": num(me["graph_ms"])},
         "per_rank_ffn_us": {"metro": me["per_rank_ffn_us"]},
         "roofline": {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(gu_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "algorithmic_bytes_per_launch": gu_b,
-                     "down_kernel": {"achieved": round(dn_b / (me["stage_us"]["down"] * 1e-6) / 1e9, 1),
-                                     "algorithmic_bytes_per_launch": dn_b}},
+                     "traffic": (rec["gate_up"]["fetch_bytes"] + rec["gate_up"]["write_bytes"]) if rec else None,
+                     "traffic_source": (f"profiles/ffn_traffic_{w.name}.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                                        f"kernel source {rec['ffn_source_sha16']})") if rec else why,
+                     "algorithmic_bytes_per_launch": gu_b,
+                     "down_kernel": {"achieved": round(dn_gbs, 1), "frac": round(dn_gbs / HBM_PEAK_GBS, 4),
+                                     "algorithmic_bytes_per_launch": dn_b,
+                                     "traffic": (rec["down"]["fetch_bytes"] + rec["down"]["write_bytes"]) if rec else None}},
     }
-    line["gate_topk"] = optional(gate_topk_timing, api, torch, W, w, x)
+    if not args.only_metro:
+        line["gate_topk"] = optional(gate_topk_timing, api, torch, W, w, x)
     if "token_balanced" in result:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)
         line["ffn_us_p10_p50_p90"]["token_balanced"] = tb["ffn_q"]
-        tb_gu = tb["bytes"][0] / (tb["stage_us"]["gate_up"] * 1e-6) / 1e9
+        tb_gu = tb["bytes"][0] / (tb["gate_up_us"] * 1e-6) / 1e9
         line["roofline"]["same_kernel_on_token_balanced_rank"] = {
             "achieved": round(tb_gu, 1), "frac": round(tb_gu / HBM_PEAK_GBS, 4),
             "algorithmic_bytes_per_launch": tb["bytes"][0], "pairs": tb["pairs"]}
-        # the comparison is only worth stating when the gap exceeds the run-to-run spread of both sides
-        gap = abs(me["ffn_q"][1] - tb["ffn_q"][1])
-        spread = max(me["ffn_q"][2] - me["ffn_q"][0], tb["ffn_q"][2] - tb["ffn_q"][0])
-        line["metro_vs_token_balanced"] = {"ffn_time_ratio": round(me["ffn_q"][1] / tb["ffn_q"][1], 3),
-                                           "conclusive": bool(gap > spread)}
+        line["metro_vs_token_balanced"] = ratio_of(result)
         line["max_activated_per_rank"]["token_balanced"] = tb["lam"]
         line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
         line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
         line["ms_per_step_token_balanced"] = round(tb["ms_per_step"], 4)
-        line["route_us_per_batch_graph_replay"]["token_balanced"] = (
-            round(tb["route_graph_us"], 2) if isinstance(tb["route_graph_us"], float) else tb["route_graph_us"])
-        line["ms_per_step_hip_graph"]["token_balanced"] = (round(tb["graph_ms"], 4) if isinstance(tb["graph_ms"], float)
-                                                           else tb["graph_ms"])
-        line["routing_sweep"] = optional(routing_sweep, api, torch, W, quick=False)
+        line["stage_us_token_balanced"] = tb["stage_us"]
+        line["route_us_per_batch_graph_replay"]["token_balanced"] = num(tb["route_graph_us"])
+        line["ms_per_step_hip_graph"]["token_balanced"] = num(tb["graph_ms"])
+    host = lambda t: t.contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+    cpu_in = None
     if not args.no_cpu_baseline:
+        g = me["rank"]
+        perm = dict(me["perm"])
+        perm["n_pairs"] = int(perm["n_pairs"][0])
+        cpu_in = (keep["ids"], keep["s2e"], host(x), host(shares[g][0]), host(shares[g][1]), perm)
+    del keep, shares, x, d_ids, d_s2e, result
+    torch.cuda.empty_cache()
+    if "token_balanced" in routings:
+        if not args.no_per_config:
+            per = {w.name: config_summary(w, {k: v for k, v in (("metro", me), ("token_balanced", tb))})}
+            for other in (W.QWEN3_235B, W.QWEN3_30B):
+                if other.name == w.name:
+                    continue
+                got = optional(lambda: config_summary(other, compare_routings(api, torch, W, other, args.steps,
+                                                                                args.warmup)[0]))
+                per[other.name] = got
+                torch.cuda.empty_cache()
+            line["per_config"] = per
+        line["routing_sweep"] = optional(routing_sweep, api, torch, W, quick=False)
+    if cpu_in is not None:
         from oracle import metro_oracle as oracle
 
         oracle.build()
-        g = me["rank"]
-        host = lambda t: t.contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
-        perm = dict(me["perm"])
-        perm["n_pairs"] = int(perm["n_pairs"][0])
-        line["cpu_baseline"] = cpu_baseline(oracle, W, w, ids, s2e, host(x), host(shares[g][0]), host(shares[g][1]),
-                                            perm, gu_b + dn_b, args.cpu_budget)
+        ids, s2e, hx, h13, h2, perm = cpu_in
+        line["cpu_baseline"] = cpu_baseline(oracle, W, w, ids, s2e, hx, h13, h2, perm, gu_b + dn_b, args.cpu_budget)
         cnt = oracle.count(ids, w.N)
         t0 = time.perf_counter()
         lam_opt = oracle.matching_opt(cnt, s2e, w.N, w.G, w.spr)
