@@ -103,12 +103,15 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
  *     topk_ids[t]  = the k experts with the largest logits, descending; equal logits: lower id first
  *     topk_w[t][j] = exp(logit[t][ids[t][j]]) / sum over the k selected of exp(logit)
  *     expert_count[e] = number of (token, expert) pairs that selected e      (T[i] of Sec. 4.1)
+ * Batches are padded to fixed sizes where the layer is replayed from a captured graph (Sec. 5): tokens
+ * t >= *n_valid are padding and get topk_ids -1 (which both routing calls skip), topk_w 0, and count nothing.
  *
  *   x        [T,H]   dtype     activations (rows H elements apart)
  *   w_gate   [N,H]   dtype     router weights, rows ldw >= H elements apart
+ *   n_valid  [1]     int32     number of real tokens, read on the device (clamped to [0, T]); NULL = T
  *   topk_ids [T,k]   int32     out; valid input for metro_route / metro_route_token_balanced
  *   topk_w   [T,k]   float32   out; valid input for moe_unpermute
- *   expert_count [N] int32     out, may be NULL
+ *   expert_count [N] int32     out, may be NULL; built by the top-k kernel itself (no extra launch)
  *   ws                         workspace of moe_gate_topk_workspace_bytes(); 256-byte aligned
  *   dtype  METRO_DTYPE_BF16: bf16 operands, fp32 accumulation on the matrix cores when H % 32 == 0,
  *          N % 64 == 0, ldw % 8 == 0 and x, w_gate are 16-byte aligned; other shapes and
@@ -118,8 +121,8 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
  */
 size_t moe_gate_topk_workspace_bytes(int T, int H, int N, int dtype);
 int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, int H, int N, int k, int dtype,
-                  int32_t* topk_ids, float* topk_w, int32_t* expert_count, void* ws, size_t ws_bytes,
-                  void* stream);
+                  const int32_t* n_valid, int32_t* topk_ids, float* topk_w, int32_t* expert_count, void* ws,
+                  size_t ws_bytes, void* stream);
 
 /*
  * moe_grouped_ffn -- SwiGLU expert FFN over the token lists of one rank.  Only slots with at

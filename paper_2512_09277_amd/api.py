@@ -66,7 +66,7 @@ def load() -> ctypes.CDLL:
         lib.moe_gate_topk_workspace_bytes.restype = sz
         lib.moe_gate_topk_workspace_bytes.argtypes = [ci, ci, ci, ci]
         lib.moe_gate_topk.restype = ci
-        lib.moe_gate_topk.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        lib.moe_gate_topk.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -260,9 +260,10 @@ def moe_unpermute(y_perm: torch.Tensor, pair_row: torch.Tensor, topk_w: torch.Te
 
 
 def moe_gate_topk(x: torch.Tensor, w_gate: torch.Tensor, k: int, out: Optional[dict] = None,
-                  ws: Optional[torch.Tensor] = None) -> dict:
+                  ws: Optional[torch.Tensor] = None, n_valid: Optional[torch.Tensor] = None) -> dict:
     """x [T,H], w_gate [N,H] (bf16 or f32; rows may be strided) -> dict(topk_ids [T,k] int32,
-    topk_w [T,k] float32, expert_count [N] int32)."""
+    topk_w [T,k] float32, expert_count [N] int32).  n_valid: int32 device tensor of one element, the number of
+    real tokens of a padded batch (tokens past it get ids -1 and weights 0)."""
     T, H = x.shape
     N = w_gate.shape[0]
     if w_gate.shape[1] != H or w_gate.stride(1) != 1:
@@ -278,7 +279,9 @@ def moe_gate_topk(x: torch.Tensor, w_gate: torch.Tensor, k: int, out: Optional[d
     if not (w_gate.is_cuda and w_gate.dtype == x.dtype):
         raise TypeError(f"w_gate: expected a {x.dtype} device tensor")
     ldw = w_gate.stride(0) if N > 1 else H
-    _check(load().moe_gate_topk(_dev(x, x.dtype, "x"), w_gate.data_ptr(), ldw, T, H, N, k, code, _dev(out["topk_ids"], torch.int32, "topk_ids"),
+    nv = None if n_valid is None else _dev(n_valid, torch.int32, "n_valid")
+    _check(load().moe_gate_topk(_dev(x, x.dtype, "x"), w_gate.data_ptr(), ldw, T, H, N, k, code, nv,
+                                _dev(out["topk_ids"], torch.int32, "topk_ids"),
                                 _dev(out["topk_w"], torch.float32, "topk_w"),
                                 _dev(out["expert_count"], torch.int32, "expert_count"),
                                 _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))

@@ -71,13 +71,13 @@ def test_host_side_argument_checks(lib):
     assert lib.moe_grouped_ffn(one, one, one, 4, 2, 3, 256, 128, 5, one, 256, one, 128, one, one, need, None) == -2
     gate_ws = lib.moe_gate_topk_workspace_bytes(32, 256, 64, 1)
     assert gate_ws >= 32 * 64 * 4
-    assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 65, 1, one, one, None, one, gate_ws, None) == -1    # k > N
-    assert lib.moe_gate_topk(one, one, 255, 32, 256, 64, 8, 1, one, one, None, one, gate_ws, None) == -1     # pitch < H
-    assert lib.moe_gate_topk(one, one, 256, 32, 256, 513, 8, 1, one, one, None, one, 1 << 20, None) == -2    # N > 512
-    assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 8, 3, one, one, None, one, gate_ws, None) == -2     # dtype
-    assert lib.moe_gate_topk(one, None, 256, 32, 256, 64, 8, 1, one, one, None, one, gate_ws, None) == -1    # null
-    assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 8, 1, one, one, None, one, gate_ws - 1, None) == -3
-    assert lib.moe_gate_topk(None, None, 256, 0, 256, 64, 8, 1, None, None, None, None, 0, None) == 0        # empty batch
+    assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 65, 1, None, one, one, None, one, gate_ws, None) == -1    # k > N
+    assert lib.moe_gate_topk(one, one, 255, 32, 256, 64, 8, 1, None, one, one, None, one, gate_ws, None) == -1     # pitch < H
+    assert lib.moe_gate_topk(one, one, 256, 32, 256, 513, 8, 1, None, one, one, None, one, 1 << 20, None) == -2    # N > 512
+    assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 8, 3, None, one, one, None, one, gate_ws, None) == -2     # dtype
+    assert lib.moe_gate_topk(one, None, 256, 32, 256, 64, 8, 1, None, one, one, None, one, gate_ws, None) == -1    # null
+    assert lib.moe_gate_topk(one, one, 256, 32, 256, 64, 8, 1, None, one, one, None, one, gate_ws - 1, None) == -3
+    assert lib.moe_gate_topk(None, None, 256, 0, 256, 64, 8, 1, None, None, None, None, None, 0, None) == 0        # empty batch
 
 
 def test_size_queries_take_every_batch_size(lib):

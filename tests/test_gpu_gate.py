@@ -135,3 +135,26 @@ def test_empty_batch_zeroes_the_counts(api):
     api.moe_gate_topk(x, dev(W.gate_weights(N, H, 81, "bf16")), k, out=out)
     torch.cuda.synchronize()
     assert (out["expert_count"] == 0).all()
+
+
+@pytest.mark.parametrize("T,n_real", [(256, 200), (1024, 1000), (64, 0), (32, 32), (16, 77)])
+def test_padded_batch(api, oracle, T, n_real):
+    """A batch padded to a fixed size (Sec. 5): tokens past *n_valid get ids -1 and weight 0 and count nothing;
+    the real tokens are exactly what the unpadded call gives.  n_valid lives on the device and is clamped to T."""
+    import torch
+
+    H, N, k = 512, 128, 8
+    x, wg = W.activations(T, H, 91, "bf16"), W.gate_weights(N, H, 92, "bf16")
+    full = api.moe_gate_topk(dev(x), dev(wg), k)
+    nv = torch.tensor([n_real], dtype=torch.int32, device="cuda")
+    got = api.moe_gate_topk(dev(x), dev(wg), k, n_valid=nv)
+    torch.cuda.synchronize()
+    n = min(n_real, T)
+    assert torch.equal(got["topk_ids"][:n], full["topk_ids"][:n]) and torch.equal(got["topk_w"][:n], full["topk_w"][:n])
+    assert (got["topk_ids"][n:] == -1).all() and (got["topk_w"][n:] == 0).all()
+    ids = got["topk_ids"][:n].cpu().numpy().reshape(-1)
+    assert np.array_equal(got["expert_count"].cpu().numpy(), np.bincount(ids, minlength=N))
+    ref = oracle.gate_topk(x[:n], wg, k, want_logits=True) if n else None
+    if n:
+        check(dict(topk_ids=got["topk_ids"][:n], topk_w=got["topk_w"][:n], expert_count=got["expert_count"]), ref, k, N,
+              "bf16")
