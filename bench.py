@@ -48,6 +48,7 @@ class HotPath:
         self.api, self.torch, self.w = api, torch, w
         self.d_ids, self.d_s2e, self.x, self.tw, self.shares = d_ids, d_s2e, x, tw, shares
         self.route_fn = api.metro_route if routing == "metro" else api.metro_route_token_balanced
+        self.fused_fn = api.metro_route_permute if routing == "metro" else api.metro_route_token_balanced_permute
         dev = x.device
         self.rb = api.route_buffers(1, w.T, w.k, w.N, w.G, dev)
         self.pb = api.permute_buffers(w.T, w.k, w.spr, dev)
@@ -77,14 +78,19 @@ class HotPath:
 
     STAGES = ["route", "permute", "gate_up", "down", "unpermute"]
 
-    def step(self, g: int, marks=None):
-        """One pass of the path.  marks: 6 events (or None entries) recorded at the stage boundaries."""
+    def step(self, g: int, marks=None, separate: bool = False):
+        """One pass of the path.  marks: 6 events (or None entries) recorded at the stage boundaries.  The routing
+        solve and the rank's token lists come from one launch (metro_route_permute); separate=True runs them as the
+        two calls, so that each can be bracketed by events."""
         api, w = self.api, self.w
         m = (lambda i: marks[i] is not None and marks[i].record()) if marks is not None else (lambda i: None)
         m(0)
-        self.route_fn(self.d_ids, self.d_s2e, w.N, w.G, w.spr, out=self.rb)
-        m(1)
-        api.moe_permute(self.rb["pair_slot"][0], g, w.spr, out=self.pb)
+        if separate:
+            self.route_fn(self.d_ids, self.d_s2e, w.N, w.G, w.spr, out=self.rb)
+            m(1)
+            api.moe_permute(self.rb["pair_slot"][0], g, w.spr, out=self.pb)
+        else:
+            self.fused_fn(self.d_ids, self.d_s2e, w.N, w.G, w.spr, g, out=self.rb, lists=self.pb)
         w13, w2 = self.weights(g)
         api.moe_grouped_ffn_stages(self.x, self.pb["perm_pair"], self.pb["group_offsets"], w.k, w13, w2, self.y,
                                    self.ws, between=lambda i: m(2 + i))
@@ -136,10 +142,16 @@ class HotPath:
         torch = self.torch
         full = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n)]
         for e in full:
+            self.step(g, e, separate=True)
+        fused = [[torch.cuda.Event(enable_timing=True), None, torch.cuda.Event(enable_timing=True), None, None, None]
+                 for _ in range(n)]
+        for e in fused:
             self.step(g, e)
         torch.cuda.synchronize()
-        return {name: 1e3 * float(np.mean([e[i].elapsed_time(e[i + 1]) for e in full]))
-                for i, name in enumerate(self.STAGES)}
+        out = {name: 1e3 * float(np.mean([e[i].elapsed_time(e[i + 1]) for e in full]))
+               for i, name in enumerate(self.STAGES)}
+        out["route_and_permute_one_launch"] = 1e3 * float(np.mean([e[0].elapsed_time(e[2]) for e in fused]))
+        return out
 
 
 def interleaved(torch, sides, steps: int, warmup: int):

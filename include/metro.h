@@ -95,6 +95,22 @@ int moe_permute(const int32_t* pair_slot, int T, int k, int rank, int spr, int32
                 int32_t* perm_pair, int32_t* pair_row, int32_t* n_pairs, void* stream);
 
 /*
+ * metro_route_permute / metro_route_token_balanced_permute -- one layer's routing solve followed, in the same
+ * launch, by the token lists of one rank ("route tokens", Sec. 4.3): exactly metro_route (or
+ * metro_route_token_balanced) with L = 1 and then moe_permute(pair_slot, rank), without the second launch --
+ * the workgroup that has just written pair_slot sorts it.  Arguments and results as in those calls;
+ * 0 <= rank < G.
+ */
+int metro_route_permute(const int32_t* topk_ids, const int32_t* slot_to_expert, int T, int k, int N, int G, int spr,
+                        int rank, int32_t* pair_slot, int32_t* expert_slot, int32_t* rank_active,
+                        uint64_t* rank_bitmap, int32_t* err_flag, int32_t* group_offsets, int32_t* perm_pair,
+                        int32_t* pair_row, int32_t* n_pairs, void* stream);
+int metro_route_token_balanced_permute(const int32_t* topk_ids, const int32_t* slot_to_expert, int T, int k, int N,
+                                       int G, int spr, int rank, int32_t* pair_slot, int32_t* rank_active,
+                                       uint64_t* rank_bitmap, int32_t* err_flag, int32_t* group_offsets,
+                                       int32_t* perm_pair, int32_t* pair_row, int32_t* n_pairs, void* stream);
+
+/*
  * moe_gate_topk -- router gate and top-k over the full (gathered) token set: the step that builds
  * the global top-k knowledge the routing solve consumes (Sec. 4.3: tokens are all-gathered and every
  * rank runs top-k on all of them).  The paper leaves the gate itself to the model; this is the

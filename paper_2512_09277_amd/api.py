@@ -23,7 +23,8 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 EXPORTS = ("metro_status_string", "metro_route", "metro_route_token_balanced", "moe_permute",
            "moe_grouped_ffn_workspace_bytes", "moe_grouped_ffn", "moe_grouped_ffn_gate_up",
            "moe_grouped_ffn_down", "moe_unpermute", "moe_gate_topk_workspace_bytes", "moe_gate_topk",
-           "moe_grouped_ffn_static_ws_bytes", "moe_grouped_ffn_static_ws")
+           "moe_grouped_ffn_static_ws_bytes", "moe_grouped_ffn_static_ws", "metro_route_permute",
+           "metro_route_token_balanced_permute")
 
 
 class MetroError(RuntimeError):
@@ -47,6 +48,10 @@ def load() -> ctypes.CDLL:
         lib.metro_route.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         lib.metro_route_token_balanced.restype = ci
         lib.metro_route_token_balanced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp]
+        lib.metro_route_permute.restype = ci
+        lib.metro_route_permute.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.metro_route_token_balanced_permute.restype = ci
+        lib.metro_route_token_balanced_permute.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.moe_permute.restype = ci
         lib.moe_permute.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp]
         lib.moe_grouped_ffn_workspace_bytes.restype = sz
@@ -170,6 +175,45 @@ def moe_permute(pair_slot: torch.Tensor, rank: int, spr: int, out=None) -> Dict[
                               _dev(out["pair_row"], torch.int32, "pair_row"),
                               _dev(out["n_pairs"], torch.int32, "n_pairs"), _stream()))
     return out
+
+
+def _route_permute(fn_name: str, topk_ids, slot_to_expert, N: int, G: int, spr: int, rank: int, out, lists):
+    if topk_ids.dim() == 3:
+        if topk_ids.shape[0] != 1:
+            raise ValueError("the fused call takes one layer")
+        topk_ids = topk_ids[0]
+    if slot_to_expert.dim() == 2:
+        slot_to_expert = slot_to_expert[0]
+    T, k = topk_ids.shape
+    if slot_to_expert.numel() != G * spr:
+        raise ValueError(f"slot_to_expert must hold G*spr={G * spr} entries")
+    if out is None:
+        out = route_buffers(1, T, k, N, G, topk_ids.device)
+    if lists is None:
+        lists = permute_buffers(T, k, spr, topk_ids.device)
+    lib = load()
+    head = [_dev(topk_ids, torch.int32, "topk_ids"), _dev(slot_to_expert, torch.int32, "slot_to_expert"), T, k, N, G, spr,
+            rank, _dev(out["pair_slot"], torch.int32, "pair_slot")]
+    tail = [_dev(out["rank_active"], torch.int32, "rank_active"), _dev(out["rank_bitmap"], torch.int64, "rank_bitmap"),
+            _dev(out["err_flag"], torch.int32, "err_flag"), _dev(lists["group_offsets"], torch.int32, "group_offsets"),
+            _dev(lists["perm_pair"], torch.int32, "perm_pair"), _dev(lists["pair_row"], torch.int32, "pair_row"),
+            _dev(lists["n_pairs"], torch.int32, "n_pairs"), _stream()]
+    if fn_name == "metro_route_permute":
+        _check(lib.metro_route_permute(*head, _dev(out["expert_slot"], torch.int32, "expert_slot"), *tail))
+    else:
+        _check(lib.metro_route_token_balanced_permute(*head, *tail))
+    return out, lists
+
+
+def metro_route_permute(topk_ids, slot_to_expert, N: int, G: int, spr: int, rank: int, out=None, lists=None):
+    """metro_route (one layer) and moe_permute(rank) in one launch -> (routing dict, token-list dict)."""
+    return _route_permute("metro_route_permute", topk_ids, slot_to_expert, N, G, spr, rank, out, lists)
+
+
+def metro_route_token_balanced_permute(topk_ids, slot_to_expert, N: int, G: int, spr: int, rank: int, out=None,
+                                       lists=None):
+    """metro_route_token_balanced (one layer) and moe_permute(rank) in one launch."""
+    return _route_permute("metro_route_token_balanced_permute", topk_ids, slot_to_expert, N, G, spr, rank, out, lists)
 
 
 def moe_grouped_ffn_workspace_bytes(T: int, k: int, spr: int, H: int, I: int, dtype: torch.dtype) -> int:

@@ -119,4 +119,60 @@ struct OrderedCounter {
     }
 };
 
+// Per-replica token lists of one rank from one layer's pair_slot (a stable counting sort by local slot), by one
+// workgroup of 1024 threads; shared by moe_permute and the routing calls that emit the lists themselves.
+//   s_hist [16 * 64], s_cnt [64], s_off [65]: LDS.  kCoherent: pair_slot was written by this workgroup a moment
+//   ago (after a device-scope fence and a barrier): read it past the L1 cache.
+constexpr int kListThreads = 1024;
+constexpr int kListMaxSpr = 64;
+template <bool kCoherent>
+__device__ __forceinline__ void build_token_lists(const int32_t* pair_slot, int n, int rank, int spr, int* s_hist,
+                                                  int* s_cnt, int* s_off, int32_t* __restrict__ group_offsets,
+                                                  int32_t* __restrict__ perm_pair, int32_t* __restrict__ pair_row,
+                                                  int32_t* __restrict__ n_pairs) {
+    const int lo = rank * spr;
+    auto key_of = [&](int p) {
+        const int slot = kCoherent ? __hip_atomic_load(pair_slot + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                   : pair_slot[p];
+        const int l = slot - lo;
+        return (l >= 0 && l < spr) ? l : -1;
+    };
+    OrderedCounter oc;
+    oc.init(n, spr, s_hist, s_cnt);
+    int keys[OrderedCounter::kCached];
+    oc.load_keys(key_of, keys);
+    __syncthreads();
+    oc.histogram(key_of, keys);
+    __syncthreads();
+    oc.prefix();
+    __syncthreads();
+    if (threadIdx.x < kWave) {                          // exclusive scan of the slot counts
+        const int c = (int)threadIdx.x < spr ? s_cnt[threadIdx.x] : 0;
+        int incl = c;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane_id() >= d) incl += up;
+        }
+        if ((int)threadIdx.x < spr) {
+            s_off[threadIdx.x] = incl - c;
+            group_offsets[threadIdx.x] = incl - c;
+        }
+        if ((int)threadIdx.x == spr - 1) {
+            s_off[spr] = incl;
+            group_offsets[spr] = incl;
+            *n_pairs = incl;
+        }
+    }
+    __syncthreads();
+    oc.number(key_of, keys, [&](int p, int l, int occ) {
+        int row = -1;
+        if (l >= 0) {
+            row = s_off[l] + occ;
+            perm_pair[row] = p;
+        }
+        pair_row[p] = row;
+    });
+}
+
 }  // namespace metro

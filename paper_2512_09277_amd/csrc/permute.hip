@@ -9,9 +9,9 @@
 namespace metro {
 namespace {
 
-constexpr int kThreads = 1024;
+constexpr int kThreads = kListThreads;
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxSpr = 64;
+constexpr int kMaxSpr = kListMaxSpr;
 
 __global__ __launch_bounds__(kThreads) void permute_kernel(const int32_t* __restrict__ pair_slot, int n, int rank,
                                                            int spr, int32_t* __restrict__ group_offsets,
@@ -21,48 +21,7 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const int32_t* __rest
     __shared__ int s_hist[kWaves * kMaxSpr];
     __shared__ int s_cnt[kMaxSpr];
     __shared__ int s_off[kMaxSpr + 1];
-    const int lo = rank * spr;
-
-    auto key_of = [&](int p) {
-        const int l = pair_slot[p] - lo;
-        return (l >= 0 && l < spr) ? l : -1;
-    };
-    OrderedCounter oc;
-    oc.init(n, spr, s_hist, s_cnt);
-    int keys[OrderedCounter::kCached];
-    oc.load_keys(key_of, keys);
-    __syncthreads();
-    oc.histogram(key_of, keys);
-    __syncthreads();
-    oc.prefix();
-    __syncthreads();
-    if (threadIdx.x < kWave) {                          // exclusive scan of the slot counts
-        const int c = threadIdx.x < spr ? s_cnt[threadIdx.x] : 0;
-        int incl = c;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int up = __shfl_up(incl, d);
-            if (lane_id() >= d) incl += up;
-        }
-        if (threadIdx.x < spr) {
-            s_off[threadIdx.x] = incl - c;
-            group_offsets[threadIdx.x] = incl - c;
-        }
-        if (threadIdx.x == spr - 1) {
-            s_off[spr] = incl;
-            group_offsets[spr] = incl;
-            *n_pairs = incl;
-        }
-    }
-    __syncthreads();
-    oc.number(key_of, keys, [&](int p, int l, int occ) {
-        int row = -1;
-        if (l >= 0) {
-            row = s_off[l] + occ;
-            perm_pair[row] = p;
-        }
-        pair_row[p] = row;
-    });
+    build_token_lists<false>(pair_slot, n, rank, spr, s_hist, s_cnt, s_off, group_offsets, perm_pair, pair_row, n_pairs);
 }
 
 }  // namespace

@@ -38,7 +38,24 @@ struct RouteArgs {
     int32_t* rank_active;
     uint64_t* rank_bitmap;
     int32_t* err_flag;
+    // token lists of one rank, emitted by the same workgroup after pair_slot (single-layer calls only)
+    int list_rank;            // < 0: no lists
+    int32_t* group_offsets;
+    int32_t* perm_pair;
+    int32_t* pair_row;
+    int32_t* n_pairs;
 };
+
+// "Route tokens" (Sec. 4.3) in the same launch: once the workgroup has written pair_slot, it builds the token
+// lists of one rank from it.  The fence makes the stores visible past this CU's L1 before the barrier.
+__device__ __forceinline__ void emit_lists(const RouteArgs& a, const int32_t* pair_slot, int n_pairs, int* s_hist,
+                                           int* s_cnt, int* s_off) {
+    if (a.list_rank < 0) return;                    // uniform
+    __threadfence();
+    __syncthreads();
+    build_token_lists<true>(pair_slot, n_pairs, a.list_rank, a.spr, s_hist, s_cnt, s_off, a.group_offsets, a.perm_pair,
+                            a.pair_row, a.n_pairs);
+}
 
 __device__ __forceinline__ uint64_t join64(uint32_t lo, uint32_t hi) { return ((uint64_t)hi << 32) | lo; }
 
@@ -69,6 +86,7 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     __shared__ uint32_t s_multi_lo[kWords], s_multi_hi[kWords];
     __shared__ uint32_t s_bm_lo[kMaxG], s_bm_hi[kMaxG];
     __shared__ int s_err;
+    __shared__ int s_list_hist[kWaves * kListMaxSpr], s_list_cnt[kListMaxSpr], s_list_off[kListMaxSpr + 1];
 
     const int layer = blockIdx.x;
     const int N = a.N, G = a.G, spr = a.spr, S = G * spr;
@@ -228,6 +246,7 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     }
     if (!a.vec4)
         for (int i = tid; i < n_pairs; i += kThreads) pair_slot[i] = slot_of(ids[i]);
+    emit_lists(a, pair_slot, n_pairs, s_list_hist, s_list_cnt, s_list_off);
 }
 
 // ------------------------------------------------------------------------------------------ token-balanced
@@ -331,6 +350,8 @@ __global__ __launch_bounds__(kThreads) void token_balanced_kernel(RouteArgs a) {
     }
     __syncthreads();
     if (tid == 0) a.err_flag[layer] = s_err;
+    // the occurrence tables are free again: the token lists reuse them
+    emit_lists(a, pair_slot, n_pairs, s_hist, s_cnt, s_base);
 }
 
 int check_route_args(const void* ids, const void* s2e, int L, int T, int k, int N, int G, int spr,
@@ -357,7 +378,20 @@ RouteArgs pack(const int32_t* ids, const int32_t* s2e, int T, int k, int N, int 
     a.rank_active = rank_active;
     a.rank_bitmap = rank_bitmap;
     a.err_flag = err_flag;
+    a.list_rank = -1;
+    a.group_offsets = a.perm_pair = a.pair_row = a.n_pairs = nullptr;
     return a;
+}
+
+int add_lists(RouteArgs& a, int rank, int32_t* group_offsets, int32_t* perm_pair, int32_t* pair_row, int32_t* n_pairs) {
+    if (!group_offsets || !n_pairs || rank < 0 || rank >= a.G) return METRO_ERR_INVALID_ARG;
+    if ((!perm_pair || !pair_row) && a.T > 0) return METRO_ERR_INVALID_ARG;
+    a.list_rank = rank;
+    a.group_offsets = group_offsets;
+    a.perm_pair = perm_pair;
+    a.pair_row = pair_row;
+    a.n_pairs = n_pairs;
+    return METRO_OK;
 }
 
 }  // namespace
@@ -388,5 +422,39 @@ extern "C" int metro_route_token_balanced(const int32_t* topk_ids, const int32_t
     RouteArgs a = pack(topk_ids, slot_to_expert, T, k, N, G, spr, pair_slot, nullptr, rank_active, rank_bitmap,
                        err_flag);
     hipLaunchKernelGGL(token_balanced_kernel, dim3(L), dim3(kThreads), 0, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
+}
+
+extern "C" int metro_route_permute(const int32_t* topk_ids, const int32_t* slot_to_expert, int T, int k, int N, int G,
+                                   int spr, int rank, int32_t* pair_slot, int32_t* expert_slot, int32_t* rank_active,
+                                   uint64_t* rank_bitmap, int32_t* err_flag, int32_t* group_offsets,
+                                   int32_t* perm_pair, int32_t* pair_row, int32_t* n_pairs, void* stream) {
+    using namespace metro;
+    int rc = check_route_args(topk_ids, slot_to_expert, 1, T, k, N, G, spr, pair_slot, rank_active, rank_bitmap,
+                              err_flag);
+    if (rc != METRO_OK) return rc;
+    if (!expert_slot) return METRO_ERR_INVALID_ARG;
+    RouteArgs a = pack(topk_ids, slot_to_expert, T, k, N, G, spr, pair_slot, expert_slot, rank_active,
+                       rank_bitmap, err_flag);
+    rc = add_lists(a, rank, group_offsets, perm_pair, pair_row, n_pairs);
+    if (rc != METRO_OK) return rc;
+    hipLaunchKernelGGL(metro_route_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
+}
+
+extern "C" int metro_route_token_balanced_permute(const int32_t* topk_ids, const int32_t* slot_to_expert, int T, int k,
+                                                  int N, int G, int spr, int rank, int32_t* pair_slot,
+                                                  int32_t* rank_active, uint64_t* rank_bitmap, int32_t* err_flag,
+                                                  int32_t* group_offsets, int32_t* perm_pair, int32_t* pair_row,
+                                                  int32_t* n_pairs, void* stream) {
+    using namespace metro;
+    int rc = check_route_args(topk_ids, slot_to_expert, 1, T, k, N, G, spr, pair_slot, rank_active, rank_bitmap,
+                              err_flag);
+    if (rc != METRO_OK) return rc;
+    RouteArgs a = pack(topk_ids, slot_to_expert, T, k, N, G, spr, pair_slot, nullptr, rank_active, rank_bitmap,
+                       err_flag);
+    rc = add_lists(a, rank, group_offsets, perm_pair, pair_row, n_pairs);
+    if (rc != METRO_OK) return rc;
+    hipLaunchKernelGGL(token_balanced_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream, a);
     return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
 }

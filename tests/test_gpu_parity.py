@@ -236,6 +236,49 @@ def test_permute_all_ranks(api, oracle, w):
             assert np.array_equal(got["pair_row"].cpu().numpy(), ref["pair_row"])
 
 
+@pytest.mark.parametrize("w", [W.TINY, W.QWEN3_30B, W.QWEN3_235B, W.DSV3], ids=lambda w: w.name)
+def test_route_and_token_lists_in_one_launch(api, oracle, w):
+    """metro_route_permute / metro_route_token_balanced_permute: the routing outputs and one rank's token lists
+    from a single launch equal the separate calls and the oracle, bit for bit, for every rank."""
+    _, s2e, ids = W.routing_inputs(w)
+    d_ids, d_s2e = dev_i32(ids), dev_i32(s2e)
+    for fused, route_ref in ((api.metro_route_permute, oracle.route_metro),
+                             (api.metro_route_token_balanced_permute, oracle.route_token_balanced)):
+        ref = route_ref(ids, s2e, w.N, w.G, w.spr)
+        for g in range(w.G):
+            out, pm = fused(d_ids, d_s2e, w.N, w.G, w.spr, g)
+            assert int(out["err_flag"].item()) == 0
+            assert np.array_equal(out["pair_slot"][0].cpu().numpy(), ref["pair_slot"])
+            assert np.array_equal(out["rank_active"][0].cpu().numpy(), ref["rank_active"])
+            assert np.array_equal(out["rank_bitmap"][0].cpu().numpy().view(np.uint64), ref["rank_bitmap"])
+            rp = oracle.permute(ref["pair_slot"], g, w.spr)
+            n = rp["n_pairs"]
+            assert int(pm["n_pairs"].item()) == n
+            assert np.array_equal(pm["group_offsets"].cpu().numpy(), rp["group_offsets"])
+            assert np.array_equal(pm["perm_pair"].cpu().numpy()[:n], rp["perm_pair"])
+            assert np.array_equal(pm["pair_row"].cpu().numpy(), rp["pair_row"])
+    # ragged pair count (no 16-byte multiple), padded pairs, an empty rank
+    rng = np.random.default_rng(5)
+    N, G, spr, k, T = 33, 5, 9, 3, 333
+    s2e = np.full(G * spr, -1, np.int32)
+    s2e[rng.permutation((G - 1) * spr)[:N]] = np.arange(N)       # the last rank hosts nothing
+    ids = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    ids[rng.random(ids.shape) < 0.1] = -1
+    for fused, route_ref in ((api.metro_route_permute, oracle.route_metro),
+                             (api.metro_route_token_balanced_permute, oracle.route_token_balanced)):
+        ref = route_ref(ids, s2e, N, G, spr)
+        for g in (0, 2, G - 1):
+            out, pm = fused(dev_i32(ids), dev_i32(s2e), N, G, spr, g)
+            rp = oracle.permute(ref["pair_slot"], g, spr)
+            assert np.array_equal(out["pair_slot"][0].cpu().numpy(), ref["pair_slot"])
+            assert int(pm["n_pairs"].item()) == rp["n_pairs"]
+            assert np.array_equal(pm["group_offsets"].cpu().numpy(), rp["group_offsets"])
+            assert np.array_equal(pm["perm_pair"].cpu().numpy()[:rp["n_pairs"]], rp["perm_pair"])
+            assert np.array_equal(pm["pair_row"].cpu().numpy(), rp["pair_row"])
+    with pytest.raises(api.MetroError):
+        api.metro_route_permute(dev_i32(ids), dev_i32(s2e), N, G, spr, G)          # rank out of range
+
+
 def test_permute_edge_cases(api, oracle):
     rng = np.random.default_rng(9)
     for T, k, spr, G in [(1, 1, 1, 1), (67, 3, 64, 2), (4096, 8, 18, 16), (5, 2, 7, 3)]:
