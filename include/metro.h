@@ -127,7 +127,7 @@ int metro_route_token_balanced_permute(const int32_t* topk_ids, const int32_t* s
  *   n_valid  [1]     int32     number of real tokens, read on the device (clamped to [0, T]); NULL = T
  *   topk_ids [T,k]   int32     out; valid input for metro_route / metro_route_token_balanced
  *   topk_w   [T,k]   float32   out; valid input for moe_unpermute
- *   expert_count [N] int32     out, may be NULL; built by the top-k kernel itself (no extra launch)
+ *   expert_count [N] int32     out, may be NULL (asking for it adds one small launch)
  *   ws                         workspace of moe_gate_topk_workspace_bytes(); 256-byte aligned
  *   dtype  METRO_DTYPE_BF16: bf16 operands, fp32 accumulation on the matrix cores when H % 32 == 0,
  *          N % 64 == 0, ldw % 8 == 0 and x, w_gate are 16-byte aligned; other shapes and

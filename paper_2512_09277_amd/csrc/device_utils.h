@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace metro {
 
 constexpr int kWave = 64;
@@ -91,13 +94,14 @@ struct OrderedCounter {
         }
     }
 
-    // emit(item, key, occ) for every item: occ = number of earlier items with the same key
-    // (key = -1: occ undefined).  Call between barriers.
+    // emit(item, key, occ, cached) for every item: occ = number of earlier items with the same key
+    // (key = -1: occ undefined); cached = index of the item's chunk among the wave's register-cached chunks
+    // (a compile-time constant there), or -1.  Call between barriers.
     template <typename KeyFn, typename EmitFn>
     __device__ __forceinline__ void number(KeyFn key_of, const int (&keys)[kCached], EmitFn emit) {
         int* mine = hist + wave_id() * n_keys;
         const int first = wave_id() * chunks_per_wave;
-        auto one_chunk = [&](int c, int key, bool in_range) {
+        auto one_chunk = [&](int c, int key, bool in_range, auto cached) {
             const bool valid = key >= 0;
             int total;
             const int rank = wave_rank_by_key(key, valid, key_bits, total);
@@ -105,42 +109,48 @@ struct OrderedCounter {
             if (valid) occ = mine[key] + rank;
             // the wave executes in lockstep: every read of mine[] above precedes the update below
             if (valid && rank == total - 1) mine[key] = occ + 1;
-            if (in_range) emit(c * kWave + lane_id(), key, occ);
+            if (in_range) emit(c * kWave + lane_id(), key, occ, cached);
         };
-#pragma unroll
-        for (int c = 0; c < kCached; ++c)
-            if (c < chunks_per_wave)                                   // uniform per wave
-                one_chunk(first + c, keys[c], (first + c) * kWave + lane_id() < n);
+        number_cached(one_chunk, keys, first, std::make_integer_sequence<int, kCached>{});
         for (int c = first + kCached; c < first + chunks_per_wave; ++c) {
             const int item = c * kWave + lane_id();
             const bool in_range = item < n;
-            one_chunk(c, in_range ? key_of(item) : -1, in_range);
+            one_chunk(c, in_range ? key_of(item) : -1, in_range, std::integral_constant<int, -1>{});
         }
+    }
+
+    template <typename ChunkFn, int... Cs>
+    __device__ __forceinline__ void number_cached(ChunkFn& one_chunk, const int (&keys)[kCached], int first,
+                                                  std::integer_sequence<int, Cs...>) {
+        // chunk index Cs is a compile-time constant, so a caller may keep per-chunk values in registers
+        ((Cs < chunks_per_wave                                        // uniform per wave
+              ? one_chunk(first + Cs, keys[Cs], (first + Cs) * kWave + lane_id() < n, std::integral_constant<int, Cs>{})
+              : (void)0),
+         ...);
     }
 };
 
-// Per-replica token lists of one rank from one layer's pair_slot (a stable counting sort by local slot), by one
-// workgroup of 1024 threads; shared by moe_permute and the routing calls that emit the lists themselves.
-//   s_hist [16 * 64], s_cnt [64], s_off [65]: LDS.  kCoherent: pair_slot was written by this workgroup a moment
-//   ago (after a device-scope fence and a barrier): read it past the L1 cache.
+// Per-replica token lists of one rank (a stable counting sort of the pairs by local slot), by one workgroup of
+// 1024 threads; shared by moe_permute and the routing calls that emit the lists themselves.
+//   key_of(p): local slot of pair p on the rank, or -1.  preset: the keys of the wave's register-cached chunks
+//   if the caller already holds them (else nullptr: they are fetched with key_of).
+//   s_hist [16 * 64], s_cnt [64], s_off [65]: LDS.
 constexpr int kListThreads = 1024;
 constexpr int kListMaxSpr = 64;
-template <bool kCoherent>
-__device__ __forceinline__ void build_token_lists(const int32_t* pair_slot, int n, int rank, int spr, int* s_hist,
+template <typename KeyFn>
+__device__ __forceinline__ void build_token_lists(KeyFn key_of, const int* preset, int n, int spr, int* s_hist,
                                                   int* s_cnt, int* s_off, int32_t* __restrict__ group_offsets,
                                                   int32_t* __restrict__ perm_pair, int32_t* __restrict__ pair_row,
                                                   int32_t* __restrict__ n_pairs) {
-    const int lo = rank * spr;
-    auto key_of = [&](int p) {
-        const int slot = kCoherent ? __hip_atomic_load(pair_slot + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                   : pair_slot[p];
-        const int l = slot - lo;
-        return (l >= 0 && l < spr) ? l : -1;
-    };
     OrderedCounter oc;
     oc.init(n, spr, s_hist, s_cnt);
     int keys[OrderedCounter::kCached];
-    oc.load_keys(key_of, keys);
+    if (preset) {
+#pragma unroll
+        for (int c = 0; c < OrderedCounter::kCached; ++c) keys[c] = preset[c];
+    } else {
+        oc.load_keys(key_of, keys);
+    }
     __syncthreads();
     oc.histogram(key_of, keys);
     __syncthreads();
@@ -165,7 +175,7 @@ __device__ __forceinline__ void build_token_lists(const int32_t* pair_slot, int 
         }
     }
     __syncthreads();
-    oc.number(key_of, keys, [&](int p, int l, int occ) {
+    oc.number(key_of, keys, [&](int p, int l, int occ, auto) {
         int row = -1;
         if (l >= 0) {
             row = s_off[l] + occ;

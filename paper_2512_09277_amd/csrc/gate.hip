@@ -12,11 +12,8 @@
 //      ~512 workgroups exist at any batch size); both operands go straight from global memory into
 //      the MFMA operand layout; fp32 partial sums land in the workspace, part[chunk][t][e];
 //   2. gate_topk_kernel: one wave per token sums the chunks in a fixed order (deterministic), picks the
-//      top-k by k rounds of a wave-wide arg-max over (logit, -id) and forms the softmax weights.  When the
-//      caller wants expert_count (T[i] of Sec. 4.1, what the routing solve tests), the same kernel builds
-//      it: an LDS histogram per workgroup of 16 tokens, written to the workspace; the workgroup that
-//      finishes last (a ticket counter) adds the histograms up in workgroup order -- no third launch, no
-//      device-scope atomics per token.
+//      top-k by k rounds of a wave-wide arg-max over (logit, -id) and forms the softmax weights;
+//   3. (only when the caller wants expert_count) gate_count_kernel: pairs per expert, one workgroup.
 // Shapes the MFMA kernel does not take (fp32, N not a multiple of 64, H not a multiple of 32) use a
 // plain one-wave-per-logit kernel in fp32.
 #include <hip/hip_runtime.h>
@@ -47,14 +44,7 @@ struct GateArgs {
     float* part;              // [n_chunks][T][N]
     int T, H, N, ldw;
     int steps_per_chunk;      // K steps of 32 per chunk
-    int* ticket;              // counter of finished top-k workgroups: set to 0 here, ahead of that kernel
 };
-
-// The first thread of the launch clears the ticket the top-k kernel counts its workgroups with (the kernel
-// boundary orders the store before every workgroup of that kernel).
-__device__ __forceinline__ void clear_ticket(const GateArgs& a) {
-    if (a.ticket && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *a.ticket = 0;
-}
 
 // One workgroup: 16*MT tokens x 64 experts x one K chunk; its four waves split the chunk's K steps and
 // meet through LDS, so one partial tile leaves the workgroup.  (Splitting K over workgroups only would
@@ -67,7 +57,6 @@ constexpr int kExpTile = 64, kNB = kExpTile / 16;
 template <int MT>
 __global__ __launch_bounds__(kThreads, 2) void gate_logits_mfma_kernel(GateArgs a) {
     __shared__ floatx4 xch[3][kNB * MT][kWave];                   // sums of waves 1..3
-    clear_ticket(a);
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r16 = lane & 15, q = lane >> 4;
     // K chunk fastest in launch order: workgroup i runs on XCD i mod 8, so with a multiple of 8 chunks
@@ -153,7 +142,6 @@ constexpr int kBigLds = 2 * kBigBuf;
 
 __global__ __launch_bounds__(kThreads, 2) void gate_logits_lds_kernel(GateArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    clear_ticket(a);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r16 = lane & 15, q = lane >> 4;
     const int chunk = blockIdx.x, t0 = blockIdx.y * kBigTile, e0 = blockIdx.z * kBigTile;
@@ -264,7 +252,6 @@ __device__ __forceinline__ float elem_f32<__bf16>(const void* p, size_t i) { ret
 // Any shape, fp32 arithmetic: one wave per logit, a single chunk.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gate_logits_general_kernel(GateArgs a) {
-    clear_ticket(a);
     const int t = blockIdx.x;
     const int e = blockIdx.y * (kThreads / kWave) + wave_id();
     if (e >= a.N) return;
@@ -282,118 +269,105 @@ struct Cand {
 };
 __device__ __forceinline__ bool better(const Cand& a, const Cand& b) { return a.v > b.v || (a.v == b.v && a.id < b.id); }
 
-// One wave per token, 16 tokens per workgroup.  Lane l holds the logits of experts l, l + 64, ... (kPerLane =
-// ceil(N / 64) of them).  Tokens at or past *n_valid (a padded batch) get ids -1 and weights 0 and count nothing.
-constexpr int kTopkThreads = 1024;
-constexpr int kTopkTokens = kTopkThreads / kWave;
+// One wave per token.  Lane l holds the logits of experts l, l + 64, ... (kPerLane = ceil(N / 64) of them).
+// Tokens at or past *n_valid (a padded batch) get ids -1 and weights 0.
 template <int kPerLane>
-__global__ __launch_bounds__(kTopkThreads) void gate_topk_kernel(const float* __restrict__ part, int n_chunks, int T,
-                                                                  int N, int k, const int32_t* __restrict__ n_valid,
-                                                                  int32_t* __restrict__ ids, float* __restrict__ w,
-                                                                  int32_t* __restrict__ cnt, int* cnt_part, int* ticket) {
-    __shared__ int hist[kMaxN];
-    __shared__ int s_last;
-    const bool counting = cnt != nullptr;                        // uniform
-    if (counting) {
-        for (int e = threadIdx.x; e < N; e += kTopkThreads) hist[e] = 0;
-        __syncthreads();
-    }
-    const int t = blockIdx.x * kTopkTokens + wave_id();
+__global__ __launch_bounds__(kThreads) void gate_topk_kernel(const float* __restrict__ part, int n_chunks, int T, int N,
+                                                              int k, const int32_t* __restrict__ n_valid,
+                                                              int32_t* __restrict__ ids, float* __restrict__ w) {
+    const int t = blockIdx.x * (kThreads / kWave) + wave_id();
+    if (t >= T) return;                                          // uniform per wave
     const int l = lane_id();
-    const int valid = n_valid ? min(max(*n_valid, 0), T) : T;
-    if (t < T && t >= valid) {                                   // padded token (uniform per wave)
+    if (n_valid && t >= min(max(*n_valid, 0), T)) {              // padded token (uniform per wave)
         if (l < k) {
             ids[(size_t)t * k + l] = -1;
             w[(size_t)t * k + l] = 0.f;
         }
-    } else if (t < T) {
-        // Chunk sums in ascending chunk order (fixed, so the result is deterministic); the loads of a batch
-        // of chunks x all of the lane's experts are issued together, only the additions are sequential.
-        float v[kPerLane];
+        return;
+    }
+    // Chunk sums in ascending chunk order (fixed, so the result is deterministic); the loads of a batch
+    // of chunks x all of the lane's experts are issued together, only the additions are sequential.
+    float v[kPerLane];
 #pragma unroll
-        for (int j = 0; j < kPerLane; ++j) v[j] = 0.f;
-        const float* row = part + (size_t)t * N + l;
-        const size_t chunk_stride = (size_t)T * N;
-        constexpr int kBatch = kPerLane <= 4 ? 8 : 4;
-        for (int c0 = 0; c0 < n_chunks; c0 += kBatch) {
-            float p[kBatch][kPerLane];
+    for (int j = 0; j < kPerLane; ++j) v[j] = 0.f;
+    const float* row = part + (size_t)t * N + l;
+    const size_t chunk_stride = (size_t)T * N;
+    constexpr int kBatch = kPerLane <= 4 ? 8 : 4;
+    for (int c0 = 0; c0 < n_chunks; c0 += kBatch) {
+        float p[kBatch][kPerLane];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int c = min(c0 + u, n_chunks - 1);         // past the end: re-read, not added
+        for (int u = 0; u < kBatch; ++u) {
+            const int c = min(c0 + u, n_chunks - 1);             // past the end: re-read, not added
 #pragma unroll
-                for (int j = 0; j < kPerLane; ++j)
-                    p[u][j] = (j * kWave + l < N) ? row[c * chunk_stride + j * kWave] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u)
-                if (c0 + u < n_chunks) {
-#pragma unroll
-                    for (int j = 0; j < kPerLane; ++j) v[j] += p[u][j];
-                }
+            for (int j = 0; j < kPerLane; ++j)
+                p[u][j] = (j * kWave + l < N) ? row[c * chunk_stride + j * kWave] : 0.f;
         }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (c0 + u < n_chunks) {
+#pragma unroll
+                for (int j = 0; j < kPerLane; ++j) v[j] += p[u][j];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        if (v[j] != v[j]) v[j] = -FLT_MAX;                       // NaN sorts below every number
+        if (j * kWave + l >= N) v[j] = -INFINITY;                // experts past N never win
+    }
+    uint32_t taken = 0;                                          // bit j: v[j] already selected
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j)
+        if (j * kWave + l >= N) taken |= 1u << j;
+    float my_v = 0.f;
+    int my_id = 0;
+    for (int r = 0; r < k; ++r) {
+        Cand best{-INFINITY, 0x7fffffff};
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
-            if (v[j] != v[j]) v[j] = -FLT_MAX;                   // NaN sorts below every number
-            if (j * kWave + l >= N) v[j] = -INFINITY;            // experts past N never win
+            const Cand c{v[j], j * kWave + l};
+            if (!((taken >> j) & 1u) && better(c, best)) best = c;
         }
-        uint32_t taken = 0;                                      // bit j: v[j] already selected
 #pragma unroll
-        for (int j = 0; j < kPerLane; ++j)
-            if (j * kWave + l >= N) taken |= 1u << j;
-        float my_v = 0.f;
-        int my_id = 0;
-        for (int r = 0; r < k; ++r) {
-            Cand best{-INFINITY, 0x7fffffff};
-#pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                const Cand c{v[j], j * kWave + l};
-                if (!((taken >> j) & 1u) && better(c, best)) best = c;
-            }
-#pragma unroll
-            for (int d = kWave / 2; d > 0; d >>= 1) {
-                const Cand o{__shfl_xor(best.v, d), __shfl_xor(best.id, d)};
-                if (better(o, best)) best = o;
-            }
-            if ((best.id & (kWave - 1)) == l) taken |= 1u << (best.id >> 6);   // k <= N: a real expert
-            if (l == r) {
-                my_v = best.v;
-                my_id = best.id;
-            }
+        for (int d = kWave / 2; d > 0; d >>= 1) {
+            const Cand o{__shfl_xor(best.v, d), __shfl_xor(best.id, d)};
+            if (better(o, best)) best = o;
         }
-        // lanes 0..k-1 hold the selection in descending order; softmax over it
-        const float top = __shfl(my_v, 0);
-        const float ex = l < k ? expf(my_v - top) : 0.f;
-        float sum = ex;
-#pragma unroll
-        for (int d = kWave / 2; d > 0; d >>= 1) sum += __shfl_xor(sum, d);
-        if (l < k) {
-            ids[(size_t)t * k + l] = my_id;
-            w[(size_t)t * k + l] = ex / sum;
-            if (counting) atomicAdd(&hist[my_id], 1);
+        if ((best.id & (kWave - 1)) == l) taken |= 1u << (best.id >> 6);   // k <= N: a real expert
+        if (l == r) {
+            my_v = best.v;
+            my_id = best.id;
         }
     }
-    if (!counting) return;                                       // uniform
-    // T[i] of Sec. 4.1: this workgroup's histogram goes to the workspace; the workgroup that takes the last
-    // ticket sees every histogram (release by the fence before the ticket, acquire by the fence after it)
-    // and adds them up in workgroup order.
-    __syncthreads();
-    for (int e = threadIdx.x; e < N; e += kTopkThreads) cnt_part[(size_t)blockIdx.x * N + e] = hist[e];
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(ticket, 1) == (int)gridDim.x - 1;
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    for (int e = threadIdx.x; e < N; e += kTopkThreads) {
-        int total = 0;
-        for (unsigned b = 0; b < gridDim.x; ++b) total += cnt_part[(size_t)b * N + e];
-        cnt[e] = total;
+    // lanes 0..k-1 hold the selection in descending order; softmax over it
+    const float top = __shfl(my_v, 0);
+    const float ex = l < k ? expf(my_v - top) : 0.f;
+    float sum = ex;
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) sum += __shfl_xor(sum, d);
+    if (l < k) {
+        ids[(size_t)t * k + l] = my_id;
+        w[(size_t)t * k + l] = ex / sum;
     }
 }
 
-// Pairs per expert of an empty batch: all zero.
-__global__ __launch_bounds__(kMaxN) void gate_zero_count_kernel(int N, int32_t* __restrict__ cnt) {
-    if ((int)threadIdx.x < N) cnt[threadIdx.x] = 0;
+// T[i] of Sec. 4.1: pairs per expert, one workgroup, LDS histogram over the ids just written (padded pairs,
+// id -1, count nothing).  A launch of its own because every way of folding it into the top-k kernel measured
+// slower at T = 1024: device-scope atomics from every token's wave onto the same few cache lines serialise
+// across the eight L2s (~10 us, more than the rest of the top-k kernel), and per-workgroup histograms added up
+// by the last workgroup to finish need a device-scope fence in every workgroup, which invalidates that XCD's
+// L2 under the workgroups still reading their partial sums (top-k kernel 10.7 -> 33.8 us).
+constexpr int kCountThreads = 1024;
+__global__ __launch_bounds__(kCountThreads) void gate_count_kernel(const int32_t* __restrict__ ids, int n_pairs, int N,
+                                                                   int32_t* __restrict__ cnt) {
+    __shared__ int hist[kMaxN];
+    for (int e = threadIdx.x; e < N; e += kCountThreads) hist[e] = 0;
+    __syncthreads();
+    for (int p = threadIdx.x; p < n_pairs; p += kCountThreads) {
+        const int e = ids[p];
+        if (e >= 0 && e < N) atomicAdd(&hist[e], 1);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < N; e += kCountThreads) cnt[e] = hist[e];
 }
 
 inline bool gate_mfma_shape(int H, int N, int dtype) {
@@ -438,23 +412,11 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 }  // namespace
 }  // namespace metro
 
-// Workspace: [fp32 partial logits: chunks x T x N][per-workgroup expert histograms: ceil(T/16) x N ints][ticket]
-namespace metro {
-namespace {
-inline size_t gate_part_bytes(int T, int H, int N, int dtype) {
-    return align256((size_t)gate_chunks(T, H, N, dtype) * T * N * sizeof(float));
-}
-inline size_t gate_hist_bytes(int T, int N) {
-    return align256((size_t)((T + kTopkTokens - 1) / kTopkTokens) * N * sizeof(int));
-}
-}  // namespace
-}  // namespace metro
-
 extern "C" size_t moe_gate_topk_workspace_bytes(int T, int H, int N, int dtype) {
     using namespace metro;
     if (T < 0 || H < 1 || N < 1) return 0;
     if (T == 0) return 256;                                       // an empty batch has no partial sums
-    return gate_part_bytes(T, H, N, dtype) + gate_hist_bytes(T, N) + 256;
+    return align256((size_t)gate_chunks(T, H, N, dtype) * T * N * sizeof(float)) + 256;
 }
 
 extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, int H, int N, int k, int dtype,
@@ -467,7 +429,8 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, 
     if (ldw < H) return METRO_ERR_INVALID_ARG;
     if (T == 0) {                                                 // no token: every expert counts zero pairs
         if (expert_count) {
-            hipLaunchKernelGGL(gate_zero_count_kernel, dim3(1), dim3(kMaxN), 0, (hipStream_t)stream, N, expert_count);
+            hipLaunchKernelGGL(gate_count_kernel, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream,
+                               (const int32_t*)nullptr, 0, N, expert_count);
             if (hipGetLastError() != hipSuccess) return METRO_ERR_HIP;
         }
         return METRO_OK;
@@ -483,9 +446,6 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, 
     a.w_gate = w_gate;
     a.part = (float*)ws;
     a.T = T; a.H = H; a.N = N; a.ldw = ldw;
-    int* cnt_part = (int*)((char*)ws + gate_part_bytes(T, H, N, dtype));
-    int* ticket = (int*)((char*)cnt_part + gate_hist_bytes(T, N));
-    a.ticket = expert_count ? ticket : nullptr;
     int n_chunks = 1;
     if (mfma) {
         a.steps_per_chunk = gate_steps_per_chunk(T, H, N);
@@ -518,15 +478,18 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int ldw, int T, 
             hipLaunchKernelGGL(gate_logits_general_kernel<__bf16>, grid, dim3(kThreads), 0, st, a);
     }
     if (hipGetLastError() != hipSuccess) return METRO_ERR_HIP;
-    const dim3 tgrid((T + kTopkTokens - 1) / kTopkTokens);
+    const int per = kThreads / kWave;
+    const dim3 tgrid((T + per - 1) / per);
     const float* part = (const float*)ws;
     auto topk = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, tgrid, dim3(kTopkThreads), 0, st, part, n_chunks, T, N, k, n_valid, topk_ids, topk_w,
-                           expert_count, cnt_part, ticket);
+        hipLaunchKernelGGL(kernel, tgrid, dim3(kThreads), 0, st, part, n_chunks, T, N, k, n_valid, topk_ids, topk_w);
     };
     if (N <= 64) topk(gate_topk_kernel<1>);
     else if (N <= 128) topk(gate_topk_kernel<2>);
     else if (N <= 256) topk(gate_topk_kernel<4>);
     else topk(gate_topk_kernel<8>);
+    if (expert_count)
+        hipLaunchKernelGGL(gate_count_kernel, dim3(1), dim3(kCountThreads), 0, st, (const int32_t*)topk_ids, T * k, N,
+                           expert_count);
     return hipGetLastError() == hipSuccess ? METRO_OK : METRO_ERR_HIP;
 }

@@ -21,7 +21,12 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const int32_t* __rest
     __shared__ int s_hist[kWaves * kMaxSpr];
     __shared__ int s_cnt[kMaxSpr];
     __shared__ int s_off[kMaxSpr + 1];
-    build_token_lists<false>(pair_slot, n, rank, spr, s_hist, s_cnt, s_off, group_offsets, perm_pair, pair_row, n_pairs);
+    const int lo = rank * spr;
+    auto key_of = [&](int p) {
+        const int l = pair_slot[p] - lo;
+        return (l >= 0 && l < spr) ? l : -1;
+    };
+    build_token_lists(key_of, nullptr, n, spr, s_hist, s_cnt, s_off, group_offsets, perm_pair, pair_row, n_pairs);
 }
 
 }  // namespace

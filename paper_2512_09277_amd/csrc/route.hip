@@ -46,17 +46,6 @@ struct RouteArgs {
     int32_t* n_pairs;
 };
 
-// "Route tokens" (Sec. 4.3) in the same launch: once the workgroup has written pair_slot, it builds the token
-// lists of one rank from it.  The fence makes the stores visible past this CU's L1 before the barrier.
-__device__ __forceinline__ void emit_lists(const RouteArgs& a, const int32_t* pair_slot, int n_pairs, int* s_hist,
-                                           int* s_cnt, int* s_off) {
-    if (a.list_rank < 0) return;                    // uniform
-    __threadfence();
-    __syncthreads();
-    build_token_lists<true>(pair_slot, n_pairs, a.list_rank, a.spr, s_hist, s_cnt, s_off, a.group_offsets, a.perm_pair,
-                            a.pair_row, a.n_pairs);
-}
-
 __device__ __forceinline__ uint64_t join64(uint32_t lo, uint32_t hi) { return ((uint64_t)hi << 32) | lo; }
 
 __device__ __forceinline__ void set_bit64(uint32_t* lo, uint32_t* hi, int idx, int bit) {
@@ -246,7 +235,18 @@ __global__ __launch_bounds__(kThreads) void metro_route_kernel(RouteArgs a) {
     }
     if (!a.vec4)
         for (int i = tid; i < n_pairs; i += kThreads) pair_slot[i] = slot_of(ids[i]);
-    emit_lists(a, pair_slot, n_pairs, s_list_hist, s_list_cnt, s_list_off);
+    // "Route tokens" (Sec. 4.3) in the same launch: the token lists of one rank.  A pair's slot is looked up from
+    // the table in LDS again (the ids come back from the cache), so nothing written above has to be re-read.
+    if (a.list_rank >= 0) {                         // uniform
+        const int lo = a.list_rank * spr;
+        auto key_of = [&](int p) {
+            const int id = ids[p];
+            const int l = ((id >= 0 && id < N) ? s_slot[id] : -1) - lo;
+            return (l >= 0 && l < spr) ? l : -1;
+        };
+        build_token_lists(key_of, nullptr, n_pairs, spr, s_list_hist, s_list_cnt, s_list_off, a.group_offsets,
+                          a.perm_pair, a.pair_row, a.n_pairs);
+    }
 }
 
 // ------------------------------------------------------------------------------------------ token-balanced
@@ -329,19 +329,30 @@ __global__ __launch_bounds__(kThreads) void token_balanced_kernel(RouteArgs a) {
         if (s_cnt[e] > 0 && s_base[e + 1] == s_base[e]) atomicOr(&s_err, METRO_FLAG_NO_REPLICA);
     __syncthreads();
 
-    // q-th pair of expert e -> replica q mod r_e.
+    // q-th pair of expert e -> replica q mod r_e.  The slots of the wave's register-cached chunks are kept for
+    // the token lists (their items map to lanes the same way there).
+    const int lo = a.list_rank * spr;
+    auto local = [&](int slot) {
+        const int l = slot - lo;
+        return (a.list_rank >= 0 && l >= 0 && l < spr) ? l : -1;
+    };
+    int list_keys[OrderedCounter::kCached];
+#pragma unroll
+    for (int c = 0; c < OrderedCounter::kCached; ++c) list_keys[c] = -1;
     oc.number(
         [&](int p) {
             const int id = ids[p];
             return (id < 0 || id >= N) ? -1 : id;
         },
-        keys, [&](int p, int e, int occ) {
+        keys, [&](int p, int e, int occ, auto cached) {
             int slot = -1;
             if (e >= 0) {
                 const int r = s_base[e + 1] - s_base[e];
                 if (r > 0) slot = s_repl[s_base[e] + occ % r];
             }
             pair_slot[p] = slot;
+            constexpr int c = decltype(cached)::value;
+            if constexpr (c >= 0) list_keys[c] = local(slot);
         });
     if (tid < G) {
         const uint64_t bm = join64(s_bm_lo[tid], s_bm_hi[tid]);
@@ -350,8 +361,18 @@ __global__ __launch_bounds__(kThreads) void token_balanced_kernel(RouteArgs a) {
     }
     __syncthreads();
     if (tid == 0) a.err_flag[layer] = s_err;
-    // the occurrence tables are free again: the token lists reuse them
-    emit_lists(a, pair_slot, n_pairs, s_hist, s_cnt, s_base);
+    // "Route tokens" (Sec. 4.3) in the same launch.  The occurrence tables are free again and the token lists reuse
+    // them.  Pairs beyond the register-cached chunks (batches of more than 8192 pairs) are read back from
+    // pair_slot: the fence pushes this workgroup's stores past the CU's L1, the loads go around it.
+    if (a.list_rank >= 0) {                         // uniform
+        __threadfence();
+        __syncthreads();
+        auto key_of = [&](int p) {
+            return local(__hip_atomic_load(pair_slot + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        };
+        build_token_lists(key_of, list_keys, n_pairs, spr, s_hist, s_cnt, s_base, a.group_offsets, a.perm_pair,
+                          a.pair_row, a.n_pairs);
+    }
 }
 
 int check_route_args(const void* ids, const void* s2e, int L, int T, int k, int N, int G, int spr,
