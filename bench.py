@@ -274,6 +274,43 @@ def gate_topk_timing(api, torch, W, w, x):
                 tflops=round(flop / us / 1e6, 1), operand_mb=round((w.T + w.N) * w.H * 2 / 1e6, 1))
 
 
+def fp32_path_timing(api, torch, W):
+    """The fp32 / odd-shape FFN path (LDS-tiled vector-ALU kernels, 1e-5 parity): expert FFN time of the busiest
+    METRO rank at the Tiny config and at the Qwen3-30B-shaped layer stored in fp32."""
+    out = {}
+    for w in (W.TINY, W.QWEN3_30B.with_(dtype="f32")):
+        _, s2e, ids = W.routing_inputs(w)
+        rb = api.metro_route(torch.from_numpy(ids).cuda(), torch.from_numpy(s2e).cuda(), w.N, w.G, w.spr)
+        ps = rb["pair_slot"][0]
+        g = int(torch.bincount((ps[ps >= 0] // w.spr).reshape(-1), minlength=w.G).argmax().item())
+        lw13, lw2 = W.device_expert_weights(w, "cuda")
+        w13, w2 = W.device_rank_share(lw13, s2e, g, w.spr), W.device_rank_share(lw2, s2e, g, w.spr)
+        del lw13, lw2
+        x = W.device_activations(w, "cuda")
+        pm = api.moe_permute(ps, g, w.spr)
+        y = torch.empty((w.T * w.k, w.H), dtype=torch.float32, device="cuda")
+        ws = torch.empty((api.moe_grouped_ffn_workspace_bytes(w.T, w.k, w.spr, w.H, w.I, torch.float32),), dtype=torch.uint8,
+                         device="cuda")
+        run = lambda: api.moe_grouped_ffn(x, pm["perm_pair"], pm["group_offsets"], w.k, w13, w2, y_perm=y, ws=ws)
+        for _ in range(5):
+            run()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 30
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            run()
+        b.record()
+        torch.cuda.synchronize()
+        us = 1e3 * a.elapsed_time(b) / n
+        sizes = torch.diff(pm["group_offsets"]).cpu().numpy()
+        active, P = int((sizes > 0).sum()), int(sizes.sum())
+        gu, dn = algorithmic_bytes(active, P, w.H, w.I, elt=4)
+        out[w.name] = dict(dtype="f32", H=w.H, I=w.I, rank=g, activated=active, pairs=P, ffn_us=round(us, 1),
+                           algorithmic_gbs=round((gu + dn) / us / 1e3, 1))
+    return out
+
+
 def routing_quality(oracle, W, sweep_rows):
     """Sec. 4.2's exact solver (binary search on lambda + bipartite matching, the oracle's CPU code) on the
     same sweep cells: mean optimal lambda next to the measured METRO / token-balanced means, METRO's gap,
@@ -569,6 +606,7 @@ def main() -> int:
     }
     if not args.only_metro:
         line["gate_topk"] = optional(gate_topk_timing, api, torch, W, w, x)
+        line["fp32_general_path"] = optional(fp32_path_timing, api, torch, W)
     if "token_balanced" in result:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)

@@ -363,7 +363,11 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ general path
-// Any shape, fp32 or bf16 storage, fp32 arithmetic: one wave per output element pair.
+// Any shape, fp32 or bf16 storage, fp32 arithmetic on the vector ALUs (the matrix-core path needs bf16 and
+// H, I multiples of 128).  One workgroup = 16 rows of one slot x 64 output columns; both operands go through LDS
+// in K steps of 32, so a weight element is fetched once per 16 rows and an activation element once per 64
+// columns (not once per output element); a thread owns 4 outputs of one row and adds its products in ascending
+// k with fused multiply-adds.
 template <typename T>
 __device__ __forceinline__ float to_f32(T v);
 template <>
@@ -381,17 +385,31 @@ __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) {
     return __builtin_bit_cast(__bf16, bits);
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d);
-    return v;
-}
+constexpr int kGenRows = 16, kGenCols = 64, kGenK = 32;
 
-__device__ __forceinline__ int slot_of_row(const int32_t* group_offsets, int spr, int r) {
-    int l = 0;
-    for (int s = 0; s < spr; ++s)
-        if (group_offsets[s] <= r && r < group_offsets[s + 1]) l = s;
-    return l;
+// Row tile `b` (counted over the slots' tiles of 16 rows, slot by slot) -> slot, first row, rows; rows = 0 past
+// the last tile.  One thread walks the <= 64 slots, the result reaches the workgroup through LDS.
+__device__ __forceinline__ void general_locate(const int32_t* __restrict__ group_offsets, int spr, int cap, int b,
+                                               int* s_tile) {
+    if (threadIdx.x == 0) {
+        int slot = 0, row0 = 0, rows = 0;
+        for (int l = 0; l < spr; ++l) {
+            const int begin = min(max(group_offsets[l], 0), cap);
+            const int m = min(max(group_offsets[l + 1], begin), cap) - begin;
+            const int nt = (m + kGenRows - 1) / kGenRows;
+            if (b < nt) {
+                slot = l;
+                row0 = begin + b * kGenRows;
+                rows = min(kGenRows, m - b * kGenRows);
+                break;
+            }
+            b -= nt;
+        }
+        s_tile[0] = slot;
+        s_tile[1] = row0;
+        s_tile[2] = rows;
+    }
+    __syncthreads();
 }
 
 template <typename T>
@@ -401,42 +419,93 @@ __global__ __launch_bounds__(kThreads) void general_gate_up_kernel(const T* __re
                                                                    int k, int spr, int H, int I,
                                                                    const T* __restrict__ w13, int ldw,
                                                                    float* __restrict__ act) {
-    const int r = blockIdx.x;                     // < T*k by the launch grid
-    if (r >= group_offsets[spr]) return;
-    const int i = blockIdx.y * (kThreads / kWave) + wave_id();
-    if (i >= I) return;
-    const int l = slot_of_row(group_offsets, spr, r);
-    const T* xr = x + (size_t)min(max(perm_pair[r] / k, 0), Tn - 1) * H;
-    const T* wg = w13 + ((size_t)l * 2 * I + i) * ldw;
-    const T* wu = wg + (size_t)I * ldw;
-    float g = 0.f, u = 0.f;
-    for (int h = lane_id(); h < H; h += kWave) {
-        const float xv = to_f32<T>(xr[h]);
-        g = fmaf(xv, to_f32<T>(wg[h]), g);
-        u = fmaf(xv, to_f32<T>(wu[h]), u);
+    __shared__ float xs[kGenRows][kGenK + 1], wg[kGenCols][kGenK + 1], wu[kGenCols][kGenK + 1];
+    __shared__ int s_tile[3], s_tok[kGenRows];
+    general_locate(group_offsets, spr, Tn * k, blockIdx.x, s_tile);
+    const int slot = s_tile[0], row0 = s_tile[1], rows = s_tile[2];
+    if (rows == 0) return;                                           // uniform
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int col0 = blockIdx.y * kGenCols;
+    if (tid < kGenRows) s_tok[tid] = min(max(perm_pair[row0 + min(tid, rows - 1)] / k, 0), Tn - 1);
+    __syncthreads();
+    const T* wslot = w13 + (size_t)slot * 2 * I * ldw;
+    float g[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < H; k0 += kGenK) {
+        for (int e = tid; e < kGenRows * kGenK; e += kThreads) {
+            const int r = e / kGenK, kk = e % kGenK;
+            xs[r][kk] = (r < rows && k0 + kk < H) ? to_f32<T>(x[(size_t)s_tok[r] * H + k0 + kk]) : 0.f;
+        }
+        for (int e = tid; e < kGenCols * kGenK; e += kThreads) {
+            const int c = e / kGenK, kk = e % kGenK;
+            const bool in = col0 + c < I && k0 + kk < H;
+            const size_t at = (size_t)(col0 + c) * ldw + k0 + kk;
+            wg[c][kk] = in ? to_f32<T>(wslot[at]) : 0.f;
+            wu[c][kk] = in ? to_f32<T>(wslot[(size_t)I * ldw + at]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int kk = 0; kk < kGenK; ++kk) {
+            const float xv = xs[ty][kk];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                g[c] = fmaf(xv, wg[tx + 16 * c][kk], g[c]);
+                u[c] = fmaf(xv, wu[tx + 16 * c][kk], u[c]);
+            }
+        }
+        __syncthreads();
     }
-    g = wave_sum(g);
-    u = wave_sum(u);
-    if (lane_id() == 0) act[(size_t)r * I + i] = g / (1.0f + expf(-g)) * u;
+    if (ty < rows) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int col = col0 + tx + 16 * c;
+            if (col < I) act[(size_t)(row0 + ty) * I + col] = g[c] / (1.0f + expf(-g[c])) * u[c];
+        }
+    }
 }
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void general_down_kernel(const float* __restrict__ act,
-                                                                const int32_t* __restrict__ group_offsets, int spr,
-                                                                int H, int I, const T* __restrict__ w2, int ldw,
+                                                                const int32_t* __restrict__ group_offsets, int cap,
+                                                                int spr, int H, int I, const T* __restrict__ w2, int ldw,
                                                                 T* __restrict__ y) {
-    const int r = blockIdx.x;
-    if (r >= group_offsets[spr]) return;
-    const int c = blockIdx.y * (kThreads / kWave) + wave_id();
-    if (c >= H) return;
-    const int l = slot_of_row(group_offsets, spr, r);
-    const float* ar = act + (size_t)r * I;
-    const T* wd = w2 + ((size_t)l * H + c) * ldw;
-    float acc = 0.f;
-    for (int i = lane_id(); i < I; i += kWave) acc = fmaf(ar[i], to_f32<T>(wd[i]), acc);
-    acc = wave_sum(acc);
-    if (lane_id() == 0) y[(size_t)r * H + c] = from_f32<T>(acc);
+    __shared__ float as[kGenRows][kGenK + 1], ws[kGenCols][kGenK + 1];
+    __shared__ int s_tile[3];
+    general_locate(group_offsets, spr, cap, blockIdx.x, s_tile);
+    const int slot = s_tile[0], row0 = s_tile[1], rows = s_tile[2];
+    if (rows == 0) return;                                           // uniform
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int col0 = blockIdx.y * kGenCols;
+    const T* wslot = w2 + (size_t)slot * H * ldw;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < I; k0 += kGenK) {
+        for (int e = tid; e < kGenRows * kGenK; e += kThreads) {
+            const int r = e / kGenK, kk = e % kGenK;
+            as[r][kk] = (r < rows && k0 + kk < I) ? act[(size_t)(row0 + r) * I + k0 + kk] : 0.f;
+        }
+        for (int e = tid; e < kGenCols * kGenK; e += kThreads) {
+            const int c = e / kGenK, kk = e % kGenK;
+            ws[c][kk] = (col0 + c < H && k0 + kk < I) ? to_f32<T>(wslot[(size_t)(col0 + c) * ldw + k0 + kk]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int kk = 0; kk < kGenK; ++kk) {
+            const float av = as[ty][kk];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] = fmaf(av, ws[tx + 16 * c][kk], acc[c]);
+        }
+        __syncthreads();
+    }
+    if (ty < rows) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int col = col0 + tx + 16 * c;
+            if (col < H) y[(size_t)(row0 + ty) * H + col] = from_f32<T>(acc[c]);
+        }
+    }
 }
+
+// Row tiles of the general path: every slot may end with a partial tile.
+inline int general_row_tiles(int cap, int spr) { return cap / kGenRows + spr; }
 
 inline bool mfma_shape(int H, int I, int dtype) {
     return dtype == METRO_DTYPE_BF16 && H % 128 == 0 && I % 128 == 0;
@@ -539,8 +608,7 @@ extern "C" int moe_grouped_ffn_gate_up(const void* x, const int32_t* perm_pair, 
     hipStream_t st = (hipStream_t)stream;
     char* act = act_of(ws);
     if (!use_mfma(T, k, H, I, dtype)) {
-        const int per = kThreads / kWave;
-        const dim3 grid(cap, (I + per - 1) / per);
+        const dim3 grid(general_row_tiles(cap, spr), (I + kGenCols - 1) / kGenCols);
         if (dtype == METRO_DTYPE_F32)
             hipLaunchKernelGGL(general_gate_up_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x,
                                perm_pair, group_offsets, T, k, spr, H, I, (const float*)w13, ldw13, (float*)act);
@@ -584,14 +652,13 @@ extern "C" int moe_grouped_ffn_down(const int32_t* group_offsets, int T, int k, 
     hipStream_t st = (hipStream_t)stream;
     char* act = act_of(ws);
     if (!use_mfma(T, k, H, I, dtype)) {
-        const int per = kThreads / kWave;
-        const dim3 grid(cap, (H + per - 1) / per);
+        const dim3 grid(general_row_tiles(cap, spr), (H + kGenCols - 1) / kGenCols);
         if (dtype == METRO_DTYPE_F32)
             hipLaunchKernelGGL(general_down_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)act,
-                               group_offsets, spr, H, I, (const float*)w2, ldw2, (float*)y_perm);
+                               group_offsets, cap, spr, H, I, (const float*)w2, ldw2, (float*)y_perm);
         else
             hipLaunchKernelGGL(general_down_kernel<__bf16>, grid, dim3(kThreads), 0, st, (const float*)act,
-                               group_offsets, spr, H, I, (const __bf16*)w2, ldw2, (__bf16*)y_perm);
+                               group_offsets, cap, spr, H, I, (const __bf16*)w2, ldw2, (__bf16*)y_perm);
         return launched();
     }
     if (enable_large_lds() != METRO_OK) return METRO_ERR_HIP;
