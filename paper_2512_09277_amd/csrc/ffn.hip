@@ -365,9 +365,9 @@ __global__ __launch_bounds__(kThreads, 2) void ffn_mfma_kernel(FfnArgs a) {
 // ------------------------------------------------------------------------------------------ general path
 // Any shape, fp32 or bf16 storage, fp32 arithmetic on the vector ALUs (the matrix-core path needs bf16 and
 // H, I multiples of 128).  One workgroup = 16 rows of one slot x 64 output columns; both operands go through LDS
-// in K steps of 32, so a weight element is fetched once per 16 rows and an activation element once per 64
-// columns (not once per output element); a thread owns 4 outputs of one row and adds its products in ascending
-// k with fused multiply-adds.
+// in K steps of 32 (the loads of the next step in flight in registers meanwhile), so a weight element is
+// fetched once per 16 rows and an activation element once per 64 columns (not once per output element); a
+// thread owns 4 outputs of one row and adds its products in ascending k with fused multiply-adds.
 template <typename T>
 __device__ __forceinline__ float to_f32(T v);
 template <>
@@ -430,19 +430,39 @@ __global__ __launch_bounds__(kThreads) void general_gate_up_kernel(const T* __re
     __syncthreads();
     const T* wslot = w13 + (size_t)slot * 2 * I * ldw;
     float g[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < H; k0 += kGenK) {
-        for (int e = tid; e < kGenRows * kGenK; e += kThreads) {
-            const int r = e / kGenK, kk = e % kGenK;
-            xs[r][kk] = (r < rows && k0 + kk < H) ? to_f32<T>(x[(size_t)s_tok[r] * H + k0 + kk]) : 0.f;
+    // the global loads of step s + 1 are in flight (in registers) while step s is multiplied out of LDS
+    constexpr int NX = kGenRows * kGenK / kThreads, NW = kGenCols * kGenK / kThreads;
+    float rx[NX], rg[NW], ru[NW];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int e = tid + j * kThreads, r = e / kGenK, kk = e % kGenK;
+            rx[j] = (r < rows && k0 + kk < H) ? to_f32<T>(x[(size_t)s_tok[r] * H + k0 + kk]) : 0.f;
         }
-        for (int e = tid; e < kGenCols * kGenK; e += kThreads) {
-            const int c = e / kGenK, kk = e % kGenK;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            const int e = tid + j * kThreads, c = e / kGenK, kk = e % kGenK;
             const bool in = col0 + c < I && k0 + kk < H;
             const size_t at = (size_t)(col0 + c) * ldw + k0 + kk;
-            wg[c][kk] = in ? to_f32<T>(wslot[at]) : 0.f;
-            wu[c][kk] = in ? to_f32<T>(wslot[(size_t)I * ldw + at]) : 0.f;
+            rg[j] = in ? to_f32<T>(wslot[at]) : 0.f;
+            ru[j] = in ? to_f32<T>(wslot[(size_t)I * ldw + at]) : 0.f;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < H; k0 += kGenK) {
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int e = tid + j * kThreads;
+            xs[e / kGenK][e % kGenK] = rx[j];
+        }
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            const int e = tid + j * kThreads;
+            wg[e / kGenK][e % kGenK] = rg[j];
+            wu[e / kGenK][e % kGenK] = ru[j];
         }
         __syncthreads();
+        if (k0 + kGenK < H) fetch(k0 + kGenK);                       // uniform
 #pragma unroll 8
         for (int kk = 0; kk < kGenK; ++kk) {
             const float xv = xs[ty][kk];
@@ -477,16 +497,34 @@ __global__ __launch_bounds__(kThreads) void general_down_kernel(const float* __r
     const int col0 = blockIdx.y * kGenCols;
     const T* wslot = w2 + (size_t)slot * H * ldw;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < I; k0 += kGenK) {
-        for (int e = tid; e < kGenRows * kGenK; e += kThreads) {
-            const int r = e / kGenK, kk = e % kGenK;
-            as[r][kk] = (r < rows && k0 + kk < I) ? act[(size_t)(row0 + r) * I + k0 + kk] : 0.f;
+    constexpr int NX = kGenRows * kGenK / kThreads, NW = kGenCols * kGenK / kThreads;
+    float ra[NX], rw[NW];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int e = tid + j * kThreads, r = e / kGenK, kk = e % kGenK;
+            ra[j] = (r < rows && k0 + kk < I) ? act[(size_t)(row0 + r) * I + k0 + kk] : 0.f;
         }
-        for (int e = tid; e < kGenCols * kGenK; e += kThreads) {
-            const int c = e / kGenK, kk = e % kGenK;
-            ws[c][kk] = (col0 + c < H && k0 + kk < I) ? to_f32<T>(wslot[(size_t)(col0 + c) * ldw + k0 + kk]) : 0.f;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            const int e = tid + j * kThreads, c = e / kGenK, kk = e % kGenK;
+            rw[j] = (col0 + c < H && k0 + kk < I) ? to_f32<T>(wslot[(size_t)(col0 + c) * ldw + k0 + kk]) : 0.f;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < I; k0 += kGenK) {
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int e = tid + j * kThreads;
+            as[e / kGenK][e % kGenK] = ra[j];
+        }
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            const int e = tid + j * kThreads;
+            ws[e / kGenK][e % kGenK] = rw[j];
         }
         __syncthreads();
+        if (k0 + kGenK < I) fetch(k0 + kGenK);                       // uniform
 #pragma unroll 8
         for (int kk = 0; kk < kGenK; ++kk) {
             const float av = as[ty][kk];
