@@ -363,10 +363,12 @@ def quantiles(v):
 
 
 def compare_routings(api, torch, W, w, steps: int, warmup: int, routings=("metro", "token_balanced"), lw=None,
-                     ranks=None, pad: bool = True, stages: bool = False):
+                     ranks=None, pad: bool = True, stages: bool = False, alone_first: bool = False):
     """One workload under the given routings: each side's slowest rank is found with all G shares resident, then
-    the sides are timed in one interleaved loop.  Returns {routing: result dict} and the objects the caller may
-    still need (inputs, the sides' HotPath objects)."""
+    the sides are timed in one interleaved loop.  alone_first: before that, the first side runs its own W + K
+    steps back to back (the benchmark's timed region: K steps of the hot path and nothing else); its figures
+    land under "alone" in that side's result.  Returns {routing: result dict} and the objects the caller may still
+    need (inputs, the sides' HotPath objects)."""
     _, s2e, ids = W.routing_inputs(w)
     d_ids = torch.from_numpy(ids).cuda().unsqueeze(0)
     d_s2e = torch.from_numpy(s2e).cuda().unsqueeze(0)
@@ -389,6 +391,9 @@ def compare_routings(api, torch, W, w, steps: int, warmup: int, routings=("metro
         if g not in keep:
             del shares[g]
     torch.cuda.empty_cache()
+    alone = None
+    if alone_first and len(sides) > 1:
+        (alone,), _ = interleaved(torch, sides[:1], steps, warmup)
     timed, wall_ms = interleaved(torch, sides, steps, warmup)
     out = {}
     for routing, (hp, g), t in zip(routings, sides, timed):
@@ -402,6 +407,13 @@ def compare_routings(api, torch, W, w, steps: int, warmup: int, routings=("metro
                             active=active, pairs=P, bytes=(gu_b, dn_b), lam=int(hp.rb["rank_active"].max().item()),
                             per_rank_ffn_us={int(k): round(v, 1) for k, v in per_rank[routing].items()},
                             stage_us=({k: round(v, 2) for k, v in hp.stage_breakdown(g).items()} if stages else None))
+    first = out[routings[0]]
+    if alone is not None:
+        ffn = alone["gate_up_us"] + alone["down_us"]
+        first["alone"] = dict(ms_per_step=alone["ms_per_step"], ffn_q=quantiles(ffn), ffn_us=float(ffn.mean()),
+                              gate_up_us=float(alone["gate_up_us"].mean()), down_us=float(alone["down_us"].mean()))
+    else:                                               # a single side was timed alone anyway
+        first["alone"] = {k: first[k] for k in ("ms_per_step", "ffn_q", "ffn_us", "gate_up_us", "down_us")}
     return out, dict(ids=ids, s2e=s2e, x=x, tw=tw, d_ids=d_ids, d_s2e=d_s2e, shares=shares, sides=dict(zip(routings, sides)),
                      wall_ms=wall_ms)
 
@@ -552,7 +564,7 @@ def main() -> int:
                 else ("metro", "token_balanced"))
     ranks = None if args.rank < 0 else [args.rank]
     result, keep = compare_routings(api, torch, W, w, args.steps, args.warmup, routings=routings, ranks=ranks,
-                                    pad=not args.dense_weights, stages=True)
+                                    pad=not args.dense_weights, stages=True, alone_first=True)
     d_ids, d_s2e, x = keep["d_ids"], keep["d_s2e"], keep["x"]
     for routing, (hp, g) in keep["sides"].items():
         r = result[routing]
@@ -568,27 +580,29 @@ def main() -> int:
                           "algorithmic_bytes_per_launch": {"gate_up": tb["bytes"][0], "down": tb["bytes"][1]}}))
         return 0
     me = result["metro"]
+    solo = me["alone"]                  # the timed region of the contract: K METRO steps back to back
     gu_b, dn_b = me["bytes"]
-    ffn_gbs = (gu_b + dn_b) / (me["ffn_us"] * 1e-6) / 1e9
-    gu_gbs = gu_b / (me["gate_up_us"] * 1e-6) / 1e9
-    dn_gbs = dn_b / (me["down_us"] * 1e-6) / 1e9
+    ffn_gbs = (gu_b + dn_b) / (solo["ffn_us"] * 1e-6) / 1e9
+    gu_gbs = gu_b / (solo["gate_up_us"] * 1e-6) / 1e9
+    dn_gbs = dn_b / (solo["down_us"] * 1e-6) / 1e9
     rec, why = recorded_traffic(w.name, "metro", me["rank"])
     shares = keep["shares"]
     num = lambda v: round(v, 4) if isinstance(v, float) else v
 
     line = {
         "metric": METRIC, "value": round(ffn_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(me["ms_per_step"], 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(solo["ms_per_step"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "E": w.N, "top_k": w.k, "G_logical_ranks": w.G, "slots_per_rank": w.spr,
                    "T": w.T, "zipf_s": w.s, "H": w.H, "I": w.I, "measured_rank": me["rank"], "routing": "metro",
                    "weight_row_pitch": {"w13": shares[me["rank"]][0].stride(1), "w2": shares[me["rank"]][1].stride(1)},
-                   "timed_loop": "METRO step and token-balanced step alternate; ms_per_step is the METRO step"
-                   if "token_balanced" in result else "METRO steps only"},
+                   "timed_loop": "value, ms_per_step, ffn_us.metro and roofline: W + K METRO steps back to back; "
+                                 "metro_vs_token_balanced, ffn_us_p10_p50_p90 and per_config: a second loop of W + K "
+                                 "iterations that alternates a METRO step and a token-balanced step"},
         "route_us_per_batch": me["stage_us"]["route"],
         "route_us_per_batch_graph_replay": {"metro": num(me["route_graph_us"])},
-        "ffn_us": {"metro": round(me["ffn_us"], 1)},
-        "ffn_us_p10_p50_p90": {"metro": me["ffn_q"]},
+        "ffn_us": {"metro": round(solo["ffn_us"], 1)},
+        "ffn_us_p10_p50_p90": {"metro": me["ffn_q"], "metro_steps_back_to_back": solo["ffn_q"]},
         "max_activated_per_rank": {"metro": me["lam"]},
         "slowest_rank": {"metro": {"rank": me["rank"], "activated": me["active"], "pairs": me["pairs"]}},
         "stage_us": me["stage_us"],
@@ -599,8 +613,11 @@ def main() -> int:
                      "traffic": (rec["gate_up"]["fetch_bytes"] + rec["gate_up"]["write_bytes"]) if rec else None,
                      "traffic_source": (f"profiles/ffn_traffic_{w.name}.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
                                         f"kernel source {rec['ffn_source_sha16']})") if rec else why,
-                     "algorithmic_bytes_per_launch": gu_b,
+                     "algorithmic_bytes_per_launch": gu_b, "launch_duration_us": round(solo["gate_up_us"], 1),
+                     "in_the_alternating_loop": {"launch_duration_us": round(me["gate_up_us"], 1),
+                                                 "frac": round(gu_b / me["gate_up_us"] / 1e3 / HBM_PEAK_GBS, 4)},
                      "down_kernel": {"achieved": round(dn_gbs, 1), "frac": round(dn_gbs / HBM_PEAK_GBS, 4),
+                                     "launch_duration_us": round(solo["down_us"], 1),
                                      "algorithmic_bytes_per_launch": dn_b,
                                      "traffic": (rec["down"]["fetch_bytes"] + rec["down"]["write_bytes"]) if rec else None}},
     }
@@ -610,6 +627,7 @@ def main() -> int:
     if "token_balanced" in result:
         tb = result["token_balanced"]
         line["ffn_us"]["token_balanced"] = round(tb["ffn_us"], 1)
+        line["ffn_us"]["metro_in_the_alternating_loop"] = round(me["ffn_us"], 1)
         line["ffn_us_p10_p50_p90"]["token_balanced"] = tb["ffn_q"]
         tb_gu = tb["bytes"][0] / (tb["gate_up_us"] * 1e-6) / 1e9
         line["roofline"]["same_kernel_on_token_balanced_rank"] = {
@@ -620,6 +638,7 @@ def main() -> int:
         line["slowest_rank"]["token_balanced"] = {"rank": tb["rank"], "activated": tb["active"], "pairs": tb["pairs"]}
         line["per_rank_ffn_us"]["token_balanced"] = tb["per_rank_ffn_us"]
         line["ms_per_step_token_balanced"] = round(tb["ms_per_step"], 4)
+        line["ms_per_step_metro_in_the_alternating_loop"] = round(me["ms_per_step"], 4)
         line["stage_us_token_balanced"] = tb["stage_us"]
         line["route_us_per_batch_graph_replay"]["token_balanced"] = num(tb["route_graph_us"])
         line["ms_per_step_hip_graph"]["token_balanced"] = num(tb["graph_ms"])

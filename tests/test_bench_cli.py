@@ -47,5 +47,9 @@ def test_bench_line_contract():
     r = d["roofline"]
     assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and 0 < r["frac"] < 1
+    pc = d["per_config"]
+    assert set(pc) == {"deepseek_v3_decode", "qwen3_235b_a22b_decode", "qwen3_30b_a3b_decode"}
+    for cfg in pc.values():
+        assert cfg["metro_vs_token_balanced"]["ffn_time_ratio"] > 0
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["unit"] == "GB/s" and c["sample"]
