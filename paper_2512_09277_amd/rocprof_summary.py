@@ -45,17 +45,22 @@ def counter_rows(path: str, counter: str):
     return rows
 
 
-def calibration(rows) -> float:
-    """Counter reading of the 1 GiB calibration copy = the last copyBuffer dispatch before this library's first kernel."""
-    last = None
-    for r in rows:
+def calibration(fetch_rows, write_rows):
+    """Counter readings of the 1 GiB calibration copy.  It is the plain copy (copyBuffer) before this library's
+    first kernel whose WRITE_SIZE is 1 GiB to within 1 % (that counter reads a plain copy exactly); the same
+    dispatch id in the FETCH_SIZE run (the same program, so the same dispatch sequence) gives the fetch reading."""
+    hit = None
+    for r in write_rows:
         if "metro::" in r["Kernel_Name"]:
             break
-        if "copyBuffer" in r["Kernel_Name"]:
-            last = float(r["Counter_Value"])
-    if last is None:
+        if "copyBuffer" in r["Kernel_Name"] and abs(float(r["Counter_Value"]) - GIB_KIB) < 0.01 * GIB_KIB:
+            hit = r
+    if hit is None:
         raise SystemExit("no calibration copy found: run bench.py with --calibration-copy")
-    return last
+    same = [r for r in fetch_rows if r["Dispatch_Id"] == hit["Dispatch_Id"] and "copyBuffer" in r["Kernel_Name"]]
+    if not same:
+        raise SystemExit("the FETCH_SIZE run has no plain copy at the calibration copy's dispatch id")
+    return float(same[0]["Counter_Value"]), float(hit["Counter_Value"])
 
 
 def per_kernel(rows):
@@ -87,7 +92,7 @@ def main() -> None:
     stats = [r for r in csv.DictReader(open(find(os.path.join(args.dir, "kt"), "*kernel_stats.csv"))) if "metro::" in r["Name"]]
     fetch = counter_rows(find(os.path.join(args.dir, "fetch"), "*counter_collection.csv"), "FETCH_SIZE")
     write = counter_rows(find(os.path.join(args.dir, "write"), "*counter_collection.csv"), "WRITE_SIZE")
-    cf, cw = calibration(fetch), calibration(write)
+    cf, cw = calibration(fetch, write)
     ff, wf = GIB_KIB / cf, GIB_KIB / cw
     f, w = per_kernel(fetch), per_kernel(write)
 
