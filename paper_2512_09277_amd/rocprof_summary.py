@@ -10,6 +10,10 @@ dispatch) and profiles/ffn_traffic_<workload>.json (the two FFN kernels' bytes p
 routing and a hash of the kernel sources they were measured on; bench.py prints them as `roofline.traffic`
 only while all three still match its own run).
 
+If <dir>/l2 exists (a fourth run, `--pmc TCC_REQ_sum TCC_HIT_sum TCC_MISS_sum TCC_EA0_RDREQ_sum`), the summary also
+lists the L2's requests, hits and misses per launch of the FFN kernels and the rate at which the misses (128 B
+each) were served over the kernel-trace duration.
+
 Byte counters are scaled by what the same counter reads for bench.py's `--calibration-copy` (one plain
 1 GiB device-to-device copy): FETCH_SIZE and WRITE_SIZE are in KiB per dispatch.
 """
@@ -71,6 +75,28 @@ def per_kernel(rows):
     return d
 
 
+L2_COUNTERS = ("TCC_REQ_sum", "TCC_HIT_sum", "TCC_MISS_sum", "TCC_EA0_RDREQ_sum")
+
+
+def l2_table(path: str, stats, cmd):
+    """L2 (TCC) requests per launch of the FFN kernels, summed over the 8 XCDs' L2s.  A request is one 128-byte
+    line; a miss becomes one read request to the fabric (TCC_EA0_RDREQ), so misses x 128 B should equal the scaled
+    FETCH_SIZE above, and misses x 128 B / duration is the rate at which the fabric filled the L2s."""
+    avg_ns = {short(r["Name"]): float(r["AverageNs"]) for r in stats}
+    vals = {c: per_kernel(counter_rows(path, c)) for c in L2_COUNTERS}
+    lines = ["", "L2 requests per dispatch (128-byte lines, all XCDs), from a fourth run:", "",
+             "    " + cmd("--pmc " + " ".join(L2_COUNTERS), "l2"), "",
+             "| kernel | requests | hits | misses | fabric read requests | miss bytes | miss bytes / avg duration |",
+             "|---|---|---|---|---|---|---|"]
+    for k in vals["TCC_REQ_sum"]:
+        if not k.startswith("ffn_mfma_kernel"):
+            continue
+        req, hit, miss, ea = (statistics.mean(vals[c][k]) for c in L2_COUNTERS)
+        lines.append(f"| {k} | {req:.4g} | {hit:.4g} | {miss:.4g} | {ea:.4g} | {miss * 128:.4g} | "
+                     f"{miss * 128 / avg_ns[k]:.0f} GB/s |")
+    return lines
+
+
 def source_sha16() -> str:
     h = hashlib.sha256()
     for name in ("ffn.hip", "device_utils.h", "host_utils.h"):
@@ -122,6 +148,9 @@ def main() -> None:
         fb, wb = fa * 1024 * ff, wa * 1024 * wf
         lines.append(f"| {k} | {len(f[k])} | {fa:.1f} | {wa:.1f} | {fb:.4g} | {wb:.4g} |")
         out[k] = dict(fetch_bytes=round(fb), write_bytes=round(wb))
+    l2_dir = os.path.join(args.dir, "l2")
+    if os.path.isdir(l2_dir):
+        lines += l2_table(find(l2_dir, "*counter_collection.csv"), stats, cmd)
     text = "\n".join(lines) + "\n"
     md = os.path.join(ROOT, "profiles", f"hot_path_{args.workload}_{args.routing}_rocprofv3.md")
     open(md, "w").write(text)
