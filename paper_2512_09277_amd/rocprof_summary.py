@@ -2,7 +2,7 @@
 
 Usage (after the three rocprofv3 runs named below wrote their CSVs under <dir>/kt, <dir>/fetch and <dir>/write):
 
-    python -m paper_2512_09277_amd.rocprof_summary --dir gpurun_out/prof --routing metro --rank 2 \\
+    python -m paper_2512_09277_amd.rocprof_summary --dir out/prof --routing metro --rank 2 \\
         --workload deepseek_v3_decode --bench-args "--only-metro --no-cpu-baseline --no-hip-graph --rank 2 --steps 20 --warmup 5 --calibration-copy"
 
 writes profiles/hot_path_<workload>_<routing>_rocprofv3.md (kernel-trace statistics and HBM-side bytes per
