@@ -437,6 +437,30 @@ def test_wide_and_stream_tiles_large_shape(api, oracle):
     run_rank(api, oracle, x, w13, w2, tw, ps, 0, spr, k, BF16_TOL)
 
 
+@pytest.mark.parametrize("dtype,H,I,k,T,sizes,tol", [
+    ("bf16", 256, 128, 8, 4096, [20000, 3, 0, 4097, 1], BF16_TOL),          # 626 + 129 tiles of 32 rows
+    ("f32", 256, 128, 8, 4096, [20000, 3, 0, 4097, 1], F32_TOL),            # general kernels, 1251 tiles of 16 rows
+    ("bf16", 4096, 2048, 2, 2048, [3000, 500, 96, 17], BF16_TOL),           # 23 + 3 full wide tiles and remainders
+], ids=["bf16-small-shape", "f32-small-shape", "bf16-large-shape"])
+def test_many_row_tiles(api, oracle, dtype, H, I, k, T, sizes, tol):
+    """A slot with far more rows than one tile holds (an expert that nearly every token of a large batch
+    picked): hundreds of row tiles in one slot, work-item ids in the thousands; every row is compared."""
+    spr = len(sizes)
+    rng = np.random.default_rng(41)
+    pairs = rng.permutation(T * k)[:sum(sizes)]
+    ps = np.full(T * k, -1, np.int32)
+    at = 0
+    for l, m in enumerate(sizes):
+        ps[pairs[at:at + m]] = l
+        at += m
+    ps = ps.reshape(T, k)
+    x = W.activations(T, H, 42, dtype)
+    w13, w2 = W.expert_weights(spr, H, I, 43, dtype)
+    tw = W.gating_weights(T, k, 44)
+    print(f"many row tiles {dtype} H={H} I={I} sizes={sizes}", flush=True)
+    run_rank(api, oracle, x, w13, w2, tw, ps, 0, spr, k, tol)
+
+
 def test_ffn_stage_calls_and_workspace_reuse(api, oracle):
     """The two stage calls (gate_up, down) equal the whole call, and a workspace can be used again
     without being cleared: the same rows come out on every pass."""
