@@ -132,7 +132,9 @@ def main() -> None:
              f"    python -m paper_2512_09277_amd.rocprof_summary --dir {args.dir} --routing {args.routing} --rank {args.rank} "
              f"--workload {args.workload} --bench-args \"...\"", "",
              "Kernel trace (every launch of a hot-path kernel in that run is on the same rank and routing, so the",
-             "average is the per-launch duration; the gate kernels come from bench.py's separate gate timing loop):", "",
+             "average is the per-launch duration" + ("; the gate kernels come from bench.py's separate gate timing loop"
+                                                     if any("gate_" in r["Name"] and "gate_up" not in r["Name"] for r in stats)
+                                                     else "") + "):", "",
              "| kernel | calls | avg ns | min ns | max ns | stddev |", "|---|---|---|---|---|---|"]
     for r in stats:
         lines.append(f"| {short(r['Name'])} | {r['Calls']} | {float(r['AverageNs']):.0f} | {r['MinNs']} | {r['MaxNs']} | "
