@@ -114,8 +114,8 @@ class HotPath:
                 for _ in range(n):
                     self.step(g)
         torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
+        for _ in range(1 + 200 // n):                    # ~0.15 s untimed: capture kept the GPU idle (see settle)
+            graph.replay()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(replays):
@@ -124,22 +124,25 @@ class HotPath:
         torch.cuda.synchronize()
         return a.elapsed_time(b) / (n * replays)
 
-    def ffn_only_us(self, g: int, iters: int = 3) -> float:
+    def ffn_only_us(self, g: int, iters: int = 5) -> float:
+        """Median gate/up + down time of `iters` steps queued back to back after ten untimed ones (the search for the
+        slowest rank).  The first handful of launches that touch a rank's weights for the first time run ~10 % slower
+        (745 us, then 662-667 us on the DeepSeek-V3-shaped METRO rank), hence the ten."""
         torch = self.torch
-        self.step(g)
-        torch.cuda.synchronize()
-        ev = [None, None] + [torch.cuda.Event(enable_timing=True) for _ in range(3)] + [None]
-        tot = 0.0
-        for _ in range(iters):
+        evs = [[None, None] + [torch.cuda.Event(enable_timing=True) for _ in range(3)] + [None] for _ in range(iters)]
+        for _ in range(10):
+            self.step(g)
+        for ev in evs:
             self.step(g, ev)
-            torch.cuda.synchronize()
-            tot += ev[2].elapsed_time(ev[4])
-        return 1e3 * tot / iters
+        torch.cuda.synchronize()
+        return 1e3 * float(np.median([ev[2].elapsed_time(ev[4]) for ev in evs]))
 
     def stage_breakdown(self, g: int, n: int = 20):
         """Mean duration of every stage from a pass that brackets each stage with events (not part of the
         timed steps: an event costs a few microseconds of stream time, which matters next to the short stages)."""
         torch = self.torch
+        for _ in range(150):                             # ~0.1 s of steps: the clocks are back up after the host-side pause
+            self.step(g)
         full = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n)]
         for e in full:
             self.step(g, e, separate=True)
@@ -187,6 +190,18 @@ def interleaved(torch, sides, steps: int, warmup: int):
     for o in out:
         o["ms_per_step"] *= scale
     return out, wall_ms
+
+
+def settle(torch, sides, seconds: float = 0.3):
+    """Untimed steps for `seconds` before a timed loop, on top of the W warm-up steps: the set-up before it (weight
+    gathers, the per-rank search with a host sync per call) leaves the first ~0.1 s of back-to-back steps 1-2 % slower
+    than the rest (gate/up 425 us, then 416 us for as long as the loop runs), and a short K would time only those."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            for hp, g in sides:
+                hp.step(g)
+        torch.cuda.synchronize()
 
 
 def graph_replay_us(torch, launch, reps: int = 20, replays: int = 10) -> float:
@@ -358,6 +373,20 @@ def cpu_baseline(oracle, W, w, ids, s2e, host_x, host_w13, host_w2, perm, ffn_by
                 ffn_us_extrapolated=round(1e6 * full_s, 1), route_us_per_batch=round(route_us, 2))
 
 
+def release_device_memory(torch):
+    """Hands the allocator's cached blocks back to the driver, then waits until the driver is done with them.
+    The driver clears released device memory in the background, and while it does the FFN kernels lose about
+    5 % of their bandwidth (gate/up of the DeepSeek-V3-shaped METRO rank: 440 us during the 1.5 s after 45 GB
+    were released, 416 us from then on; 0.6 s after 22 GB).  Timed regions therefore never follow a release
+    directly: either nothing is released before them (the cache is kept), or this wait comes first."""
+    before = torch.cuda.memory_reserved()
+    torch.cuda.empty_cache()
+    freed = before - torch.cuda.memory_reserved()
+    torch.cuda.synchronize()
+    if freed > 0:
+        time.sleep(0.5 + freed / 15e9)
+
+
 def quantiles(v):
     return [round(float(np.percentile(v, q)), 1) for q in (10, 50, 90)]
 
@@ -382,6 +411,7 @@ def compare_routings(api, torch, W, w, steps: int, warmup: int, routings=("metro
     sides, per_rank = [], {}
     for routing in routings:
         hp = HotPath(api, torch, w, d_ids, d_s2e, x, tw, shares, routing)
+        settle(torch, [(hp, ranks[0])])
         per_rank[routing] = {g: hp.ffn_only_us(g) for g in ranks}
         g = max(per_rank[routing], key=per_rank[routing].get)
         hp.copies = {g: hp.copies[g]}
@@ -389,8 +419,8 @@ def compare_routings(api, torch, W, w, steps: int, warmup: int, routings=("metro
     keep = {g for _, g in sides}
     for g in list(shares):
         if g not in keep:
-            del shares[g]
-    torch.cuda.empty_cache()
+            del shares[g]                                # back to the allocator's cache, not to the driver
+    settle(torch, sides)
     alone = None
     if alone_first and len(sides) > 1:
         (alone,), _ = interleaved(torch, sides[:1], steps, warmup)
@@ -462,9 +492,9 @@ def replication_sweep(api, torch, W, steps: int, warmup: int):
                 rows.append(cell)
                 print(json.dumps(cell), file=sys.stderr, flush=True)
                 del keep, res
-                torch.cuda.empty_cache()
+                release_device_memory(torch)
         del lw
-        torch.cuda.empty_cache()
+        release_device_memory(torch)
     return rows
 
 
@@ -649,8 +679,7 @@ def main() -> int:
         perm = dict(me["perm"])
         perm["n_pairs"] = int(perm["n_pairs"][0])
         cpu_in = (keep["ids"], keep["s2e"], host(x), host(shares[g][0]), host(shares[g][1]), perm)
-    del keep, shares, x, d_ids, d_s2e, result
-    torch.cuda.empty_cache()
+    del keep, shares, x, d_ids, d_s2e, result           # stays in the allocator's cache for the runs below
     if "token_balanced" in routings:
         if not args.no_per_config:
             per = {w.name: config_summary(w, {k: v for k, v in (("metro", me), ("token_balanced", tb))})}
@@ -660,7 +689,6 @@ def main() -> int:
                 got = optional(lambda: config_summary(other, compare_routings(api, torch, W, other, args.steps,
                                                                                 args.warmup)[0]))
                 per[other.name] = got
-                torch.cuda.empty_cache()
             line["per_config"] = per
         line["routing_sweep"] = optional(routing_sweep, api, torch, W, quick=False)
     if cpu_in is not None:
