@@ -14,6 +14,10 @@ METRO routing; the route latency, FFN times under both routers, the roofline of 
 METRO and token-balanced routing are compared inside one timed loop that alternates a METRO step and a
 token-balanced step (each on its own slowest rank), so that clock and power drift hit both sides alike; the
 same comparison at the two Qwen3-shaped configs rides along in `per_config`.
+
+Every timed loop runs W warm-up steps and then exactly K timed steps; before that come 0.3 s of untimed steps, and
+no device memory is handed back to the driver until the timed work is done (see `settle` and
+`release_device_memory` for what each of these keeps out of the timed region).
 """
 from __future__ import annotations
 
